@@ -1,0 +1,163 @@
+"""CPU oracle: full-model greedy decoding and greedy self-speculative decoding.
+
+TEST INFRASTRUCTURE ONLY (see decoder.py).
+
+`greedy_full` is the plain definition of the result: autoregressive greedy decoding with
+all L layers (the "Autoregressive" baseline of Section 6.2).
+
+`self_speculative` takes the steps of Section 4.3 in the paper's order and notation:
+  self-drafting (4.3.1): d tokens D_0..D_{d-1}, autoregressively, exiting at layer E;
+  self-verification (4.3.2): the remaining L-E layers predict the next token for every
+    draft position in ONE pass, continuing from the cached exit-layer states (4.3.3) and
+    sharing the draft's KV cache; drafts up to the first disagreement are kept, then the
+    verified token at the disagreement is appended;
+  cache crop (Appendix A.4): the cache keeps (prompt + emitted - 1) positions, i.e. the
+    last emitted token has not been through the model yet.
+Readings taken where the paper leaves room:
+  * verification consumes 1 + d rows (the round's input token and the d drafts), as the
+    appendix passes "input + draft tokens" to the remainder; so the last draft needs its
+    own early-layer pass (no LM head) and a round emits n+1 tokens, n = accepted drafts;
+  * the cached "exit query" is the hidden state x_E of each drafted position;
+  * the prompt is prefilled with the full model, whose greedy token is output #1;
+  * the output is cut to exactly n_new tokens; acceptance counts the uncut n.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+
+from .decoder import OracleModel, KVCache, argmax_lowest, top2_margin
+
+
+@dataclass
+class RoundTrace:
+    pos: int                   # cache length at the start of the round
+    last: int                  # the round's input token (emitted, not yet in the cache)
+    draft: List[int]
+    verify: List[int]
+    n_accept: int
+    draft_margins: List[float]
+    verify_margins: List[float]
+
+
+@dataclass
+class DecodeResult:
+    tokens: List[int]
+    margins: List[float]                    # top-1 minus top-2 of the logits that chose each token
+    rounds: List[RoundTrace] = field(default_factory=list)
+    drafted: int = 0
+    accepted: int = 0
+    hidden: Optional[np.ndarray] = None     # [L+1, positions, d_model] when requested
+
+    @property
+    def acceptance(self) -> float:
+        return self.accepted / self.drafted if self.drafted else 0.0
+
+
+def prefill(model: OracleModel, prompt, cache: KVCache, hidden=None):
+    """All L layers over the prompt rows; returns the logits of the last row."""
+    pos = list(range(len(prompt)))
+    x = model.embed_tokens(prompt)
+    if hidden is not None:
+        hidden.append(x.copy())
+    x = model.run_layers(x, pos, cache, 0, model.cfg.n_layers, hidden)
+    return model.head(x[-1:])[0]
+
+
+def greedy_full(model: OracleModel, prompt, n_new: int, max_seq: Optional[int] = None,
+                want_hidden: bool = False) -> DecodeResult:
+    """t_0 = argmax g(x_L[P-1]); t_k = argmax g(x_L) after feeding t_{k-1} at position P+k-1."""
+    L = model.cfg.n_layers
+    P = len(prompt)
+    cache = model.new_cache(max_seq or (P + n_new + 1))
+    hid = [] if want_hidden else None
+    logits = prefill(model, prompt, cache, hid)
+    per_pos = None
+    if want_hidden:
+        per_pos = [np.stack(hid, axis=0)]            # [L+1, P, dm]
+    tokens, margins = [argmax_lowest(logits)], [top2_margin(logits)]
+    while len(tokens) < n_new:
+        t = P + len(tokens) - 1
+        x = model.embed_tokens([tokens[-1]])
+        h = [x.copy()] if want_hidden else None
+        x = model.run_layers(x, [t], cache, 0, L, h)
+        if want_hidden:
+            per_pos.append(np.stack(h, axis=0))
+        logits = model.head(x)[0]
+        tokens.append(argmax_lowest(logits))
+        margins.append(top2_margin(logits))
+    res = DecodeResult(tokens, margins)
+    if want_hidden:
+        res.hidden = np.concatenate(per_pos, axis=1)
+    return res
+
+
+def self_speculative(model: OracleModel, prompt, n_new: int, exit_layer: int, d: int,
+                     max_seq: Optional[int] = None, round_hook=None) -> DecodeResult:
+    """Greedy self-speculative decoding, Section 4.3 / Appendix A.4.
+
+    round_hook(cache, pos, out) is called after every round (tests use it to inspect the cache).
+    """
+    L, E = model.cfg.n_layers, exit_layer
+    assert 1 <= E <= L and d >= 1
+    P = len(prompt)
+    cache = model.new_cache(max_seq or (P + n_new + d + 1))
+    logits = prefill(model, prompt, cache)
+    out, margins = [argmax_lowest(logits)], [top2_margin(logits)]
+    pos, last = P, out[0]
+    res = DecodeResult(out, margins)
+    while len(out) < n_new:
+        # self-drafting: d early-exit steps; X[i] is the exit state x_E of the i-th row
+        D, dm_, X = [], [], []
+        u = last
+        for i in range(d):
+            x = model.run_layers(model.embed_tokens([u]), [pos + i], cache, 0, E)
+            X.append(x[0])
+            lg = model.head(x)[0]                       # early exit: g(x_E)
+            D.append(argmax_lowest(lg))
+            dm_.append(top2_margin(lg))
+            u = D[-1]
+        # the last draft has not been an input yet: early layers only, no head
+        x = model.run_layers(model.embed_tokens([D[-1]]), [pos + d], cache, 0, E)
+        X.append(x[0])
+        # self-verification: layers E..L-1 over the 1+d rows in one pass
+        rows = np.stack(X, axis=0)
+        xl = model.run_layers(rows, list(range(pos, pos + d + 1)), cache, E, L)
+        lg = model.head(xl)
+        V = [argmax_lowest(lg[i]) for i in range(d + 1)]
+        vm = [top2_margin(lg[i]) for i in range(d + 1)]
+        # acceptance: longest prefix of drafts equal to the verified tokens
+        n = 0
+        while n < d and D[n] == V[n]:
+            n += 1
+        emitted = D[:n] + [V[n]]
+        emitted_m = vm[:n + 1]
+        res.rounds.append(RoundTrace(pos, last, D, V, n, dm_, vm))
+        res.drafted += d
+        res.accepted += n
+        room = n_new - len(out)
+        out.extend(emitted[:room])
+        margins.extend(emitted_m[:room])
+        pos += n + 1          # crop: positions beyond pos are dead and get overwritten
+        last = V[n]
+        if round_hook is not None:
+            round_hook(cache, pos, list(out))
+    return res
+
+
+def early_exit_greedy(model: OracleModel, prompt, n_new: int, exit_layer: int) -> DecodeResult:
+    """Section 4.2 on its own: every token is argmax g(x_E); the late layers never run."""
+    E, P = exit_layer, len(prompt)
+    cache = model.new_cache(P + n_new + 1)
+    x = model.run_layers(model.embed_tokens(prompt), list(range(P)), cache, 0, E)
+    logits = model.head(x[-1:])[0]
+    tokens, margins = [argmax_lowest(logits)], [top2_margin(logits)]
+    while len(tokens) < n_new:
+        t = P + len(tokens) - 1
+        x = model.run_layers(model.embed_tokens([tokens[-1]]), [t], cache, 0, E)
+        logits = model.head(x)[0]
+        tokens.append(argmax_lowest(logits))
+        margins.append(top2_margin(logits))
+    return DecodeResult(tokens, margins)

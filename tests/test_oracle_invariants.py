@@ -1,0 +1,155 @@
+"""Pins for the oracle's decoding loops: the invariants the method fixes.
+
+* Self-speculative greedy output equals full-model greedy output (Section 4.3.2: the full
+  model corrects the drafts, so there is no change in output).
+* E = L: the draft already ran every layer, so every draft is accepted (Sections 2.1, 4.2).
+* Zero residual scale on layers >= E: x_L = x_E (Section 4.1 recurrence), so acceptance is
+  100 % and the number of rounds has a closed form.
+* Brute force: recomputing the whole sequence without a cache gives the same ids / states.
+* After every crop the cache equals a fresh prefill of prompt + emitted[:-1] (Appendix A.4).
+"""
+import math
+
+import numpy as np
+import pytest
+
+import oracle as O
+import workloads as W
+
+
+def _model(c1, dtype=np.float64, **kw):
+    w, ws, p = c1
+    return w, O.OracleModel(w.model, ws, dtype, **kw), p
+
+
+@pytest.mark.parametrize("E,d", [(1, 1), (2, 4), (3, 7), (2, 15), (4, 3), (1, 12)])
+def test_self_speculative_equals_full_greedy(c1, E, d):
+    w, m, p = _model(c1)
+    g = O.greedy_full(m, p, w.n_new)
+    s = O.self_speculative(m, p, w.n_new, E, d)
+    assert s.tokens == g.tokens
+    assert len(s.tokens) == w.n_new
+    # accounting (Appendix A.4): every round emits its accepted drafts plus one verified token
+    assert 1 + sum(r.n_accept + 1 for r in s.rounds) >= w.n_new
+    assert 1 + sum(r.n_accept + 1 for r in s.rounds[:-1]) < w.n_new
+    assert s.drafted == d * len(s.rounds) and 0 <= s.accepted <= s.drafted
+    for r in s.rounds:
+        assert r.draft[:r.n_accept] == r.verify[:r.n_accept]
+        assert r.n_accept == d or r.draft[r.n_accept] != r.verify[r.n_accept]
+
+
+def test_float32_oracle_is_lossless_too(c1):
+    w, m, p = _model(c1, np.float32)
+    g = O.greedy_full(m, p, w.n_new)
+    s = O.self_speculative(m, p, w.n_new, w.exit_layer, w.draft_len)
+    firm = [i for i, mg in enumerate(g.margins) if mg < 1e-4]
+    upto = firm[0] if firm else w.n_new
+    assert s.tokens[:upto] == g.tokens[:upto]
+
+
+def test_exit_at_last_layer_accepts_every_draft(c1):
+    w, m, p = _model(c1)
+    s = O.self_speculative(m, p, 40, w.model.n_layers, 5)
+    assert all(r.n_accept == 5 for r in s.rounds)
+    assert s.acceptance == 1.0
+    assert s.tokens == O.greedy_full(m, p, 40).tokens
+    assert O.early_exit_greedy(m, p, 40, w.model.n_layers).tokens == s.tokens
+
+
+@pytest.mark.parametrize("d", [1, 4, 6])
+def test_zero_residual_scale_closed_form(d):
+    w = W.get_workload("c1").with_(resid_scale=0.0)
+    ws, p = W.make_weights(w), W.make_prompt(w)
+    m = O.OracleModel(w.model, ws, np.float64)
+    N = 50
+    s = O.self_speculative(m, p, N, w.exit_layer, d)
+    assert s.acceptance == 1.0
+    assert len(s.rounds) == math.ceil((N - 1) / (d + 1))
+    assert s.tokens == O.greedy_full(m, p, N).tokens
+    assert s.tokens == O.early_exit_greedy(m, p, N, w.exit_layer).tokens
+
+
+def test_brute_force_without_cache_gives_same_ids_and_states(c1):
+    w, m, p = _model(c1)
+    N = 12
+    g = O.greedy_full(m, p, N, want_hidden=True)
+    assert O.greedy_nocache(m, p, N) == g.tokens
+    hidden, logits = O.forward_nocache(m, list(p) + g.tokens[:-1])
+    assert g.hidden.shape == hidden.shape == (w.model.n_layers + 1, len(p) + N - 1, w.model.d_model)
+    np.testing.assert_allclose(g.hidden, hidden, rtol=1e-9, atol=1e-12)
+    assert [int(np.argmax(logits[len(p) - 1 + i])) for i in range(N)] == g.tokens
+
+
+def test_brute_force_matches_with_bf16_emulation():
+    w = W.get_workload("c1")
+    w = w.with_(model=W.ModelConfig(**{**w.model.__dict__, "dtype": "bf16", "name": "c1-bf16"}))
+    ws, p = W.make_weights(w), W.make_prompt(w)
+    m = O.OracleModel(w.model, ws, np.float32, emulate_bf16_act=True)
+    g = O.greedy_full(m, p, 10)
+    firm = [i for i, mg in enumerate(g.margins) if mg < 1e-3]
+    upto = firm[0] if firm else 10
+    assert O.greedy_nocache(m, p, 10)[:upto] == g.tokens[:upto]
+    s = O.self_speculative(m, p, 10, 2, 4)
+    assert s.tokens[:upto] == g.tokens[:upto]
+
+
+def test_cache_after_each_crop_equals_fresh_prefill(c1):
+    w, m, p = _model(c1)
+    P, L = len(p), w.model.n_layers
+    seen = []
+
+    def hook(cache, pos, out):
+        if len(out) < 30:                                    # untruncated rounds only
+            assert pos == P + len(out) - 1
+        fresh = m.new_cache(cache.max_seq)
+        seq = list(p) + out[:-1]
+        n = min(pos, len(seq))
+        O.prefill(m, seq[:n], fresh)
+        np.testing.assert_allclose(cache.k[:, :, :n], fresh.k[:, :, :n], rtol=1e-9, atol=1e-12)
+        np.testing.assert_allclose(cache.v[:, :, :n], fresh.v[:, :, :n], rtol=1e-9, atol=1e-12)
+        seen.append(pos)
+
+    s = O.self_speculative(m, p, 30, 2, 4, round_hook=hook)
+    assert len(seen) == len(s.rounds) and seen == sorted(seen)
+    for r0, r1 in zip(s.rounds, s.rounds[1:]):
+        assert r1.pos == r0.pos + r0.n_accept + 1 and r1.last == r0.verify[r0.n_accept]
+
+
+def test_acceptance_does_not_fall_with_deeper_exit(c1):
+    """Trend the paper reports (Section 6.2, task-specific finetuning: acceptance grows with E)."""
+    w, ws, p = c1
+    acc = []
+    for E in (1, 2, 3, 4):
+        wE = W.make_weights(w, exit_layer=E)
+        m = O.OracleModel(w.model, wE, np.float64)
+        acc.append(O.self_speculative(m, p, 64, E, 4).acceptance)
+    assert acc[-1] == 1.0 and acc[0] <= acc[1] + 0.05 <= acc[-1] + 0.1
+
+
+# ---------------------------------------------------------------- the pins do catch mistakes
+MISTAKES = {
+    "rope sign": ("apply_rope", lambda y, c, s: np.concatenate(
+        [y[..., :y.shape[-1] // 2] * c[:, None, :] + y[..., y.shape[-1] // 2:] * s[:, None, :],
+         y[..., y.shape[-1] // 2:] * c[:, None, :] - y[..., :y.shape[-1] // 2] * s[:, None, :]], -1)),
+    "norm drops gain": ("rmsnorm", lambda x, g, eps: x / np.sqrt(np.mean(x * x, -1, keepdims=True) + eps)),
+    "norm drops eps": ("rmsnorm", lambda x, g, eps: x / np.sqrt(np.mean(x * x, -1, keepdims=True)) * g),
+    "silu is sigmoid": ("silu", lambda z: 1.0 / (1.0 + np.exp(-z))),
+    "softmax unnormalised": ("softmax_lastaxis", lambda s: np.exp(s - s.max(-1, keepdims=True))),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MISTAKES))
+def test_planted_mistake_in_oracle_is_caught_by_brute_force_or_closed_forms(name, monkeypatch):
+    """Plant one mistake in the cached decoder; the no-cache brute force (written separately)
+    or the component closed forms must disagree."""
+    import oracle.decoder as dec
+    fn, bad = MISTAKES[name]
+    w = W.get_workload("c1").with_(gain_jitter=0.2)
+    ws, p = W.make_weights(w), W.make_prompt(w, 8)
+    m = O.OracleModel(w.model, ws, np.float64)
+    monkeypatch.setattr(dec, fn, bad)
+    cache = m.new_cache(16)
+    x = m.run_layers(m.embed_tokens(p), range(8), cache, 0, 2)
+    monkeypatch.undo()
+    ref = O.forward_nocache(m, p, n_layers=2)[0][-1]
+    assert np.max(np.abs(x - ref)) > 1e-6
