@@ -1,0 +1,165 @@
+/*
+ * ls.h - C ABI of the MI355X (gfx950) library for greedy self-speculative decoding with
+ * early-exit drafts on a Llama-style decoder, batch 1, one GPU.
+ *
+ * Method (paper sections, restated in our words):
+ *   - Section 4.1: the decoder is x_{l+1} = x_l + f_l(x_l) for l = 0..L-1; the LM head g is the
+ *     final normalisation followed by the final linear layer (Section 2.1) and is shared by
+ *     every exit.
+ *   - Section 4.2: an early exit at E runs layers 0..E-1 and predicts with g(x_E).
+ *   - Section 4.3.1 (self-drafting): d tokens are drafted autoregressively with the early exit.
+ *   - Section 4.3.2 (self-verification): layers E..L-1 predict, in one pass, the token after
+ *     each of the 1+d rows (the round's input token and the d drafts); drafts are kept up to
+ *     the first disagreement and the verified token at that point is appended.
+ *   - Section 4.3.3 (cache reuse): one KV cache for both stages, plus the exit-layer states of
+ *     the drafted positions so that verification starts at layer E.
+ *   - Appendix A.4: after a round the cache keeps (prompt + emitted - 1) positions.
+ *
+ * Conventions
+ *   - Pointers marked DEVICE point to GPU memory the CALLER owns (weights, workspace, token
+ *     buffers).  The library never allocates or frees device memory.  Pointers marked HOST are
+ *     ordinary host memory.  `stream` is a hipStream_t passed as void* (NULL = default stream).
+ *   - Matrices are row-major [out_features, in_features]; dtype is LS_F32 or LS_BF16 for all
+ *     weights, the KV cache and the matmul inputs; accumulation, the residual stream, softmax
+ *     and logits are fp32.
+ *   - Every function returns LS_OK (0) or a negative LS_E_* code; none aborts or throws.
+ *     Arguments are validated before anything is enqueued, so LS_E_ARG / LS_E_RANGE /
+ *     LS_E_CAPACITY / LS_E_STATE never leave work on the stream.
+ *   - ls_prefill / ls_draft / ls_verify only ENQUEUE on `stream`; their results live in device
+ *     state.  ls_generate, ls_score, ls_get_state and ls_peek_round synchronise the stream.
+ *   - One context is one sequence: calls on one context must not overlap in time.
+ */
+#ifndef LS_H_
+#define LS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ls_ctx ls_ctx; /* opaque host object */
+
+enum { LS_F32 = 0, LS_BF16 = 1 };
+
+enum {
+  LS_OK = 0,
+  LS_E_ARG = -1,      /* null pointer, unsupported shape or dtype                           */
+  LS_E_RANGE = -2,    /* exit_layer outside [1, L], d outside [0, max_draft], bad counts    */
+  LS_E_CAPACITY = -3, /* workspace too small, or the sequence would not fit in max_seq      */
+  LS_E_STATE = -4,    /* call order: draft before prefill, verify without a matching draft  */
+  LS_E_HIP = -5,      /* a HIP runtime call failed                                          */
+  LS_E_DEVICE = -6    /* the device reported an error (bounded wait expired, capacity)      */
+};
+
+#define LS_MAX_ROWS 16 /* rows per pass: 1 + max_draft <= 16 */
+
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
+  float rope_base, rms_eps;
+  int32_t dtype;     /* LS_F32 or LS_BF16                                                   */
+  int32_t max_seq;   /* KV capacity in positions                                            */
+  int32_t max_draft; /* 1..15                                                               */
+} ls_config;
+/* Supported shapes: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads with ratio <= 4;
+ * d_model, ffn_dim, n_q_heads*head_dim multiples of 16; vocab a multiple of 16. */
+
+typedef struct { /* all DEVICE pointers; the per-layer arrays are HOST arrays of DEVICE pointers */
+  const void *embed;                                  /* [vocab, d_model]                   */
+  const void *const *wq, *const *wk, *const *wv;      /* [n_q*hd, dm], [n_kv*hd, dm] x2      */
+  const void *const *wo;                              /* [dm, n_q*hd]                        */
+  const void *const *w_gate, *const *w_up;            /* [ffn, dm]                           */
+  const void *const *w_down;                          /* [dm, ffn]                           */
+  const void *const *attn_norm, *const *ffn_norm;     /* [dm] RMSNorm gains                  */
+  const void *final_norm;                             /* [dm]                                */
+  const void *lm_head;                                /* [vocab, dm] (not tied to embed)     */
+} ls_weights;
+
+typedef struct {
+  int64_t rounds;    /* draft+verify rounds run (0 for full-model greedy)                    */
+  int64_t drafted;   /* d per round                                                          */
+  int64_t accepted;  /* drafts kept by verification; acceptance rate = accepted / drafted    */
+  int64_t generated; /* tokens written to the output                                         */
+  float ms_prefill;  /* device time of the prefill, from events on `stream`                  */
+  float ms_decode;   /* device time of everything after the prefill                          */
+} ls_stats;
+
+/* Bytes of DEVICE workspace ls_load_weights needs for this configuration (KV cache, exit-state
+ * rows, per-stage scratch, rotary table, device state).  0 if the configuration is invalid. */
+size_t ls_workspace_bytes(const ls_config *cfg);
+
+/* Creates a context.  `weights` pointers are kept (not copied) and must outlive the context;
+ * `dev_workspace` (DEVICE, 256-byte aligned, >= ls_workspace_bytes) is owned by the caller and
+ * used exclusively by this context.  Uploads the rotary table and the layer pointer table into
+ * the workspace (synchronously) and zeroes the device state.  *out is the new context. */
+int ls_load_weights(const ls_config *cfg, const ls_weights *weights, void *dev_workspace,
+                    size_t workspace_bytes, ls_ctx **out);
+
+/* Prefill: all L layers over the n_prompt prompt ids (DEVICE int32[n_prompt]); fills the KV cache
+ * at positions [0, n_prompt) and takes the first generated token t_0 = argmax g(x_L[n_prompt-1]).
+ * Resets the decoding state to {pos = n_prompt, last = t_0, n_gen = 1}.  Enqueue only.
+ * The prompt buffer must stay valid until the stream has run the call. */
+int ls_prefill(ls_ctx *ctx, const int32_t *dev_prompt, int32_t n_prompt, void *stream);
+
+/* Self-drafting (Section 4.3.1): d early-exit steps through layers 0..exit_layer-1, each followed
+ * by the shared head and an argmax, giving D_0..D_{d-1}; then the early layers once more for
+ * D_{d-1} (no head), so that the exit-state rows 0..d are complete.  Appends K,V of layers
+ * < exit_layer at positions pos..pos+d.  Enqueue only.  d >= 1. */
+int ls_draft(ls_ctx *ctx, int32_t exit_layer, int32_t d, void *stream);
+
+/* Self-verification (Section 4.3.2) + acceptance + cache crop (Appendix A.4): layers
+ * exit_layer..L-1 over the 1+d exit-state rows in one pass, head + argmax per row giving
+ * V_0..V_d; n = number of leading drafts with D_i == V_i; the round emits D_0..D_{n-1}, V_n;
+ * pos += n+1, last = V_n.  Must follow ls_draft with the same (exit_layer, d).  Enqueue only. */
+int ls_verify(ls_ctx *ctx, int32_t exit_layer, int32_t d, void *stream);
+
+/* Whole job: prefill, then rounds of draft+verify until max_new tokens exist (the first comes
+ * from the prefill), all enqueued without host round-trips; d = 0 runs full-model greedy
+ * decoding instead (the autoregressive baseline).  Stops early after emitting eos_id (pass -1
+ * for none).  dev_out_tokens: DEVICE int32[max_new], unused tail filled with -1.
+ * host_stats (HOST, may be NULL) receives the counters.  Synchronises `stream`. */
+int ls_generate(ls_ctx *ctx, const int32_t *dev_prompt, int32_t n_prompt, int32_t max_new,
+                int32_t exit_layer, int32_t d, int32_t eos_id, int32_t *dev_out_tokens,
+                ls_stats *host_stats, void *stream);
+
+/* Early exit on its own (Section 4.2): like ls_generate with d = 0, but every pass, the prefill
+ * included, runs layers 0..exit_layer-1 only and predicts with g(x_E). */
+int ls_generate_early_exit(ls_ctx *ctx, const int32_t *dev_prompt, int32_t n_prompt,
+                           int32_t max_new, int32_t exit_layer, int32_t *dev_out_tokens,
+                           ls_stats *host_stats, void *stream);
+
+/* Inspection: teacher-forced scoring.  Runs layers 0..n_layers_used-1 (1..L) over n tokens
+ * (DEVICE int32[n]) as one causal sequence from position 0 and writes, for every row, the argmax
+ * of g(x) (DEVICE int32[n]) and, if dev_margin is not NULL, top-1 minus top-2 of its logits
+ * (DEVICE float[n]).  Overwrites the KV cache and invalidates the decoding state.  Synchronises. */
+int ls_score(ls_ctx *ctx, const int32_t *dev_tokens, int32_t n, int32_t n_layers_used,
+             int32_t *dev_argmax, float *dev_margin, void *stream);
+
+/* Inspection: synchronises `stream` and returns the decoding state (HOST out-pointers, any may
+ * be NULL).  Returns LS_E_DEVICE if the device flagged an error. */
+int ls_get_state(ls_ctx *ctx, int32_t *pos, int32_t *last, int32_t *n_gen, void *stream);
+
+/* Inspection: synchronises and copies out the last round: drafts (HOST int32[d]), verified
+ * tokens (HOST int32[d+1]), their logit margins (HOST float[d], float[d+1]; may be NULL) and the
+ * number of accepted drafts. */
+int ls_peek_round(ls_ctx *ctx, int32_t *host_draft, int32_t *host_verify, float *host_draft_margin,
+                  float *host_verify_margin, int32_t *n_accept, void *stream);
+
+/* Inspection: from now on every pass also stores x_{l+1} of each row it computes at
+ * dev_hidden[l][position][:] (DEVICE float [n_layers][max_seq][d_model]); NULL switches it off. */
+int ls_debug_capture(ls_ctx *ctx, float *dev_hidden);
+
+/* Launch shape: workgroups per compute unit (1 or 2) used by later calls; 0 restores the default.
+ * Returns the number of workgroups a launch will use, or a negative error. */
+int ls_set_launch(ls_ctx *ctx, int32_t workgroups_per_cu);
+
+const char *ls_strerror(int code);
+
+/* Frees the host object only; the workspace and the weights stay with the caller. */
+void ls_destroy(ls_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LS_H_ */

@@ -1,0 +1,400 @@
+// Host side of the C ABI declared in include/ls.h: argument validation, workspace layout,
+// program set-up and launches of the persistent kernel.  No device memory is allocated here;
+// everything lives in the caller's workspace.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/ls.h"
+#include "ls_internal.h"
+
+extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid, hipStream_t stream);
+extern "C" int ls_kernel_setup(int dtype_is_bf16, int* max_blocks_per_cu);
+
+namespace {
+
+struct Layout {
+  size_t layers, rope_cos, rope_sin, kcache, vcache, xbuf, ssq, qbuf, obuf, actbuf, attn_part, attn_cnt, cand, bar,
+      state, total;
+};
+
+constexpr int kMaxGrid = 1024;
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+bool config_ok(const ls_config* c) {
+  if (!c) return false;
+  if (c->dtype != LS_F32 && c->dtype != LS_BF16) return false;
+  if (c->n_layers < 1 || c->n_layers > 4096) return false;
+  if (c->head_dim != 64 && c->head_dim != 128) return false;
+  if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads) return false;
+  if (c->n_q_heads / c->n_kv_heads > 4) return false;
+  if (c->d_model < 16 || c->d_model % 16 || c->ffn_dim < 16 || c->ffn_dim % 16) return false;
+  if (c->vocab < 16 || c->vocab % 16) return false;
+  if (c->max_draft < 1 || c->max_draft > LS_MAX_ROWS - 1) return false;
+  if (c->max_seq < 2 || c->max_seq > (1 << 20)) return false;
+  if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f)) return false;
+  return true;
+}
+
+Layout make_layout(const ls_config* c) {
+  Layout L{};
+  const size_t esz = c->dtype == LS_BF16 ? 2 : 4;
+  const size_t qd = (size_t)c->n_q_heads * c->head_dim, kvd = (size_t)c->n_kv_heads * c->head_dim;
+  const size_t max_tiles = ((size_t)c->max_seq + LS_ATTN_TILE - 1) / LS_ATTN_TILE;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  L.layers = take(sizeof(LsLayerW) * c->n_layers);
+  L.rope_cos = take(sizeof(float) * c->max_seq * (c->head_dim / 2));
+  L.rope_sin = take(sizeof(float) * c->max_seq * (c->head_dim / 2));
+  L.kcache = take(esz * c->n_layers * kvd * c->max_seq);
+  L.vcache = take(esz * c->n_layers * kvd * c->max_seq);
+  L.xbuf = take(sizeof(float) * LS_ROWS * c->d_model);
+  L.ssq = take(sizeof(float) * LS_ROWS * (c->d_model / 16));
+  L.qbuf = take(esz * LS_ROWS * qd);
+  L.obuf = take(esz * LS_ROWS * qd);
+  L.actbuf = take(esz * LS_ROWS * c->ffn_dim);
+  L.attn_part = take(sizeof(float) * c->n_kv_heads * max_tiles * 64 * (c->head_dim + 2));
+  L.attn_cnt = take(sizeof(uint32_t) * c->n_kv_heads);
+  L.cand = take(sizeof(float) * 4 * LS_ROWS * kMaxGrid);
+  L.bar = take(256);
+  L.state = take(sizeof(LsState));
+  L.total = off;
+  return L;
+}
+
+}  // namespace
+
+struct ls_ctx {
+  ls_config cfg;
+  Layout lay;
+  char* ws;
+  LsKParams base;   // model + workspace part of the kernel parameters
+  int n_cu, max_wg_per_cu, wg_per_cu, grid;
+  bool prefilled, drafted;
+  int draft_E, draft_d;
+  int pos_bound;    // upper bound of the device-side position, for capacity checks
+  hipEvent_t ev[3];
+  float* capture;
+};
+
+namespace {
+
+int choose_nt(int units, int grid, bool pairs) {
+  // tiles per workgroup pass: as many as keeps at least `grid` groups, but never fewer than one unit
+  const int opts_single[3] = {4, 2, 1};
+  const int opts_pair[2] = {4, 2};
+  if (pairs) {
+    for (int nt : opts_pair)
+      if ((units + nt / 2 - 1) / (nt / 2) >= grid) return nt;
+    return 2;
+  }
+  for (int nt : opts_single)
+    if ((units + nt - 1) / nt >= grid) return nt;
+  return 1;
+}
+
+void set_decomposition(ls_ctx* c) {
+  const ls_config& g = c->cfg;
+  const int pph = g.head_dim / 32;
+  const int qkv_items = (g.n_q_heads + g.n_kv_heads) * pph + g.n_kv_heads * g.head_dim / 32;
+  c->base.nt_qkv = choose_nt(qkv_items, c->grid, true);
+  c->base.nt_o = choose_nt(g.d_model / 16, c->grid, false);
+  c->base.nt_gu = choose_nt(g.ffn_dim / 16, c->grid, true);
+  c->base.nt_down = c->base.nt_o;
+}
+
+int launch(ls_ctx* c, LsKParams& p, hipStream_t s) {
+  if (hipMemsetAsync(p.bar, 0, 256, s) != hipSuccess) return LS_E_HIP;
+  if (ls_launch_program(&p, c->cfg.dtype == LS_BF16, c->grid, s) != 0) return LS_E_HIP;
+  return LS_OK;
+}
+
+LsKParams program(const ls_ctx* c, int kind) {
+  LsKParams p = c->base;
+  p.kind = kind;
+  p.E = 0; p.d = 0; p.max_new = 0x7fffffff; p.eos = -1; p.n_tokens = 0; p.layers_used = c->cfg.n_layers;
+  p.tokens = nullptr; p.out_tokens = nullptr; p.out_margin = nullptr;
+  p.capture = c->capture;
+  return p;
+}
+
+int read_state(ls_ctx* c, LsState* st, hipStream_t s) {
+  if (hipMemcpyAsync(st, c->base.state, sizeof(LsState), hipMemcpyDeviceToHost, s) != hipSuccess) return LS_E_HIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return LS_E_HIP;
+  return LS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ls_workspace_bytes(const ls_config* cfg) {
+  if (!config_ok(cfg)) return 0;
+  return make_layout(cfg).total;
+}
+
+int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspace, size_t workspace_bytes,
+                    ls_ctx** out) {
+  if (!out) return LS_E_ARG;
+  *out = nullptr;
+  if (!config_ok(cfg) || !w || !dev_workspace) return LS_E_ARG;
+  if ((uintptr_t)dev_workspace % 256) return LS_E_ARG;
+  if (!w->embed || !w->final_norm || !w->lm_head || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate || !w->w_up ||
+      !w->w_down || !w->attn_norm || !w->ffn_norm)
+    return LS_E_ARG;
+  auto bad = [](const void* p) { return p == nullptr || ((uintptr_t)p % 16) != 0; };
+  if (bad(w->embed) || bad(w->final_norm) || bad(w->lm_head)) return LS_E_ARG;
+  for (int l = 0; l < cfg->n_layers; ++l)
+    if (bad(w->wq[l]) || bad(w->wk[l]) || bad(w->wv[l]) || bad(w->wo[l]) || bad(w->w_gate[l]) || bad(w->w_up[l]) ||
+        bad(w->w_down[l]) || bad(w->attn_norm[l]) || bad(w->ffn_norm[l]))
+      return LS_E_ARG;
+  const Layout lay = make_layout(cfg);
+  if (workspace_bytes < lay.total) return LS_E_CAPACITY;
+
+  ls_ctx* c = new (std::nothrow) ls_ctx();
+  if (!c) return LS_E_ARG;
+  c->cfg = *cfg;
+  c->lay = lay;
+  c->ws = static_cast<char*>(dev_workspace);
+  c->capture = nullptr;
+  c->prefilled = c->drafted = false;
+  c->pos_bound = 0;
+
+  hipDeviceProp_t prop;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) { delete c; return LS_E_HIP; }
+  c->n_cu = prop.multiProcessorCount;
+  int nb = 0;
+  if (ls_kernel_setup(cfg->dtype == LS_BF16, &nb) != 0 || nb < 1) { delete c; return LS_E_HIP; }
+  c->max_wg_per_cu = nb > 2 ? 2 : nb;
+  c->wg_per_cu = c->max_wg_per_cu;
+  if (const char* e = getenv("LS_WG_PER_CU")) {
+    const int v = atoi(e);
+    if (v >= 1 && v <= c->max_wg_per_cu) c->wg_per_cu = v;
+  }
+  c->grid = c->n_cu * c->wg_per_cu;
+  if (c->grid > kMaxGrid) c->grid = kMaxGrid;
+
+  // layer pointer table and rotary table
+  std::vector<LsLayerW> lw(cfg->n_layers);
+  for (int l = 0; l < cfg->n_layers; ++l)
+    lw[l] = LsLayerW{w->wq[l], w->wk[l], w->wv[l], w->wo[l], w->w_gate[l], w->w_up[l], w->w_down[l],
+                     w->attn_norm[l], w->ffn_norm[l]};
+  const int half = cfg->head_dim / 2;
+  std::vector<float> cs((size_t)cfg->max_seq * half), sn((size_t)cfg->max_seq * half);
+  for (int j = 0; j < half; ++j) {
+    const double inv_freq = std::pow((double)cfg->rope_base, -2.0 * j / cfg->head_dim);
+    for (int t = 0; t < cfg->max_seq; ++t) {
+      const double a = (double)t * inv_freq;
+      cs[(size_t)t * half + j] = (float)std::cos(a);
+      sn[(size_t)t * half + j] = (float)std::sin(a);
+    }
+  }
+  bool okc = hipMemcpy(c->ws + lay.layers, lw.data(), sizeof(LsLayerW) * lw.size(), hipMemcpyHostToDevice) == hipSuccess;
+  okc = okc && hipMemcpy(c->ws + lay.rope_cos, cs.data(), sizeof(float) * cs.size(), hipMemcpyHostToDevice) == hipSuccess;
+  okc = okc && hipMemcpy(c->ws + lay.rope_sin, sn.data(), sizeof(float) * sn.size(), hipMemcpyHostToDevice) == hipSuccess;
+  okc = okc && hipMemset(c->ws + lay.xbuf, 0, lay.total - lay.xbuf) == hipSuccess;
+  okc = okc && hipDeviceSynchronize() == hipSuccess;
+  for (int i = 0; i < 3 && okc; ++i) okc = hipEventCreate(&c->ev[i]) == hipSuccess;
+  if (!okc) { delete c; return LS_E_HIP; }
+
+  LsKParams& p = c->base;
+  memset(&p, 0, sizeof(p));
+  p.L = cfg->n_layers; p.dm = cfg->d_model; p.nq = cfg->n_q_heads; p.nkv = cfg->n_kv_heads; p.hd = cfg->head_dim;
+  p.ffn = cfg->ffn_dim; p.vocab = cfg->vocab; p.qd = cfg->n_q_heads * cfg->head_dim;
+  p.kvd = cfg->n_kv_heads * cfg->head_dim; p.G = cfg->n_q_heads / cfg->n_kv_heads; p.max_seq = cfg->max_seq;
+  p.eps = cfg->rms_eps;
+  p.attn_scale = (float)(1.0 / std::sqrt((double)cfg->head_dim));
+  p.layers = reinterpret_cast<const LsLayerW*>(c->ws + lay.layers);
+  p.embed = w->embed; p.final_norm = w->final_norm; p.lm_head = w->lm_head;
+  p.rope_cos = reinterpret_cast<const float*>(c->ws + lay.rope_cos);
+  p.rope_sin = reinterpret_cast<const float*>(c->ws + lay.rope_sin);
+  p.kcache = c->ws + lay.kcache; p.vcache = c->ws + lay.vcache;
+  p.xbuf = reinterpret_cast<float*>(c->ws + lay.xbuf);
+  p.ssq = reinterpret_cast<float*>(c->ws + lay.ssq);
+  p.qbuf = c->ws + lay.qbuf; p.obuf = c->ws + lay.obuf; p.actbuf = c->ws + lay.actbuf;
+  p.attn_part = reinterpret_cast<float*>(c->ws + lay.attn_part);
+  p.attn_cnt = reinterpret_cast<uint32_t*>(c->ws + lay.attn_cnt);
+  p.max_tiles = (cfg->max_seq + LS_ATTN_TILE - 1) / LS_ATTN_TILE;
+  p.cand = reinterpret_cast<float*>(c->ws + lay.cand);
+  p.bar = reinterpret_cast<uint32_t*>(c->ws + lay.bar);
+  p.state = reinterpret_cast<LsState*>(c->ws + lay.state);
+  p.spin_limit = 1 << 22;
+  if (const char* e = getenv("LS_SPIN_LIMIT")) { const int v = atoi(e); if (v > 0) p.spin_limit = v; }
+  set_decomposition(c);
+  *out = c;
+  return LS_OK;
+}
+
+int ls_set_launch(ls_ctx* c, int32_t wg_per_cu) {
+  if (!c) return LS_E_ARG;
+  if (wg_per_cu < 0 || wg_per_cu > c->max_wg_per_cu) return LS_E_RANGE;
+  c->wg_per_cu = wg_per_cu == 0 ? c->max_wg_per_cu : wg_per_cu;
+  c->grid = c->n_cu * c->wg_per_cu;
+  if (c->grid > kMaxGrid) c->grid = kMaxGrid;
+  set_decomposition(c);
+  return c->grid;
+}
+
+int ls_prefill(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, void* stream) {
+  if (!c || !dev_prompt) return LS_E_ARG;
+  if (n_prompt < 1) return LS_E_RANGE;
+  if (n_prompt + 1 > c->cfg.max_seq) return LS_E_CAPACITY;
+  LsKParams p = program(c, LS_PROG_PREFILL);
+  p.tokens = dev_prompt; p.n_tokens = n_prompt;
+  const int rc = launch(c, p, static_cast<hipStream_t>(stream));
+  if (rc != LS_OK) return rc;
+  c->prefilled = true; c->drafted = false; c->pos_bound = n_prompt;
+  return LS_OK;
+}
+
+int ls_draft(ls_ctx* c, int32_t E, int32_t d, void* stream) {
+  if (!c) return LS_E_ARG;
+  if (E < 1 || E > c->cfg.n_layers || d < 1 || d > c->cfg.max_draft) return LS_E_RANGE;
+  if (!c->prefilled) return LS_E_STATE;
+  if (c->pos_bound + d + 1 > c->cfg.max_seq) return LS_E_CAPACITY;
+  LsKParams p = program(c, LS_PROG_DRAFT);
+  p.E = E; p.d = d;
+  const int rc = launch(c, p, static_cast<hipStream_t>(stream));
+  if (rc != LS_OK) return rc;
+  c->drafted = true; c->draft_E = E; c->draft_d = d;
+  return LS_OK;
+}
+
+int ls_verify(ls_ctx* c, int32_t E, int32_t d, void* stream) {
+  if (!c) return LS_E_ARG;
+  if (E < 1 || E > c->cfg.n_layers || d < 1 || d > c->cfg.max_draft) return LS_E_RANGE;
+  if (!c->prefilled || !c->drafted || c->draft_E != E || c->draft_d != d) return LS_E_STATE;
+  LsKParams p = program(c, LS_PROG_VERIFY);
+  p.E = E; p.d = d;
+  const int rc = launch(c, p, static_cast<hipStream_t>(stream));
+  if (rc != LS_OK) return rc;
+  c->drafted = false;
+  c->pos_bound += d + 1;
+  return LS_OK;
+}
+
+static int generate_impl(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, int32_t max_new, int32_t E, int32_t d,
+                         int32_t eos, int32_t layers_used, int32_t* dev_out, ls_stats* stats, void* stream) {
+  if (!c || !dev_prompt || !dev_out) return LS_E_ARG;
+  if (n_prompt < 1 || max_new < 1) return LS_E_RANGE;
+  if (d < 0 || d > c->cfg.max_draft) return LS_E_RANGE;
+  if (d > 0 && (E < 1 || E > c->cfg.n_layers)) return LS_E_RANGE;
+  if (layers_used < 1 || layers_used > c->cfg.n_layers) return LS_E_RANGE;
+  if ((long)n_prompt + max_new + d + 1 > c->cfg.max_seq) return LS_E_CAPACITY;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (hipMemsetAsync(dev_out, 0xFF, sizeof(int32_t) * max_new, s) != hipSuccess) return LS_E_HIP;
+  if (hipEventRecord(c->ev[0], s) != hipSuccess) return LS_E_HIP;
+  LsKParams p = program(c, LS_PROG_PREFILL);
+  p.tokens = dev_prompt; p.n_tokens = n_prompt; p.out_tokens = dev_out; p.eos = eos; p.max_new = max_new;
+  p.layers_used = layers_used;
+  int rc = launch(c, p, s);
+  if (rc != LS_OK) return rc;
+  if (hipEventRecord(c->ev[1], s) != hipSuccess) return LS_E_HIP;
+  LsKParams g = program(c, LS_PROG_GENERATE);
+  g.E = E; g.d = d; g.max_new = max_new; g.eos = eos; g.out_tokens = dev_out; g.layers_used = layers_used;
+  rc = launch(c, g, s);
+  if (rc != LS_OK) return rc;
+  if (hipEventRecord(c->ev[2], s) != hipSuccess) return LS_E_HIP;
+  LsState st;
+  rc = read_state(c, &st, s);
+  if (rc != LS_OK) return rc;
+  c->prefilled = true; c->drafted = false; c->pos_bound = st.pos;
+  if (stats) {
+    stats->rounds = st.rounds; stats->drafted = st.drafted; stats->accepted = st.accepted; stats->generated = st.n_gen;
+    stats->ms_prefill = stats->ms_decode = 0.f;
+    (void)hipEventElapsedTime(&stats->ms_prefill, c->ev[0], c->ev[1]);
+    (void)hipEventElapsedTime(&stats->ms_decode, c->ev[1], c->ev[2]);
+  }
+  return st.error ? LS_E_DEVICE : LS_OK;
+}
+
+int ls_generate(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, int32_t max_new, int32_t E, int32_t d,
+                int32_t eos, int32_t* dev_out, ls_stats* stats, void* stream) {
+  if (!c) return LS_E_ARG;
+  return generate_impl(c, dev_prompt, n_prompt, max_new, E, d, eos, c->cfg.n_layers, dev_out, stats, stream);
+}
+
+int ls_generate_early_exit(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, int32_t max_new, int32_t E,
+                           int32_t* dev_out, ls_stats* stats, void* stream) {
+  if (!c) return LS_E_ARG;
+  if (E < 1 || E > c->cfg.n_layers) return LS_E_RANGE;
+  return generate_impl(c, dev_prompt, n_prompt, max_new, E, 0, -1, E, dev_out, stats, stream);
+}
+
+int ls_score(ls_ctx* c, const int32_t* dev_tokens, int32_t n, int32_t layers_used, int32_t* dev_argmax,
+             float* dev_margin, void* stream) {
+  if (!c || !dev_tokens || !dev_argmax) return LS_E_ARG;
+  if (n < 1 || layers_used < 1 || layers_used > c->cfg.n_layers) return LS_E_RANGE;
+  if (n > c->cfg.max_seq) return LS_E_CAPACITY;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  LsKParams p = program(c, LS_PROG_SCORE);
+  p.tokens = dev_tokens; p.n_tokens = n; p.layers_used = layers_used; p.out_tokens = dev_argmax; p.out_margin = dev_margin;
+  int rc = launch(c, p, s);
+  if (rc != LS_OK) return rc;
+  c->prefilled = false; c->drafted = false;
+  LsState st;
+  rc = read_state(c, &st, s);
+  if (rc != LS_OK) return rc;
+  return st.error ? LS_E_DEVICE : LS_OK;
+}
+
+int ls_get_state(ls_ctx* c, int32_t* pos, int32_t* last, int32_t* n_gen, void* stream) {
+  if (!c) return LS_E_ARG;
+  LsState st;
+  const int rc = read_state(c, &st, static_cast<hipStream_t>(stream));
+  if (rc != LS_OK) return rc;
+  if (pos) *pos = st.pos;
+  if (last) *last = st.last;
+  if (n_gen) *n_gen = st.n_gen;
+  c->pos_bound = st.pos;
+  return st.error ? LS_E_DEVICE : LS_OK;
+}
+
+int ls_peek_round(ls_ctx* c, int32_t* hd, int32_t* hv, float* hdm, float* hvm, int32_t* n_accept, void* stream) {
+  if (!c) return LS_E_ARG;
+  LsState st;
+  const int rc = read_state(c, &st, static_cast<hipStream_t>(stream));
+  if (rc != LS_OK) return rc;
+  const int d = st.draft_valid ? st.draft_d : c->draft_d;
+  if (d < 1 || d > LS_ROWS - 1) return LS_E_STATE;
+  if (hd) memcpy(hd, st.D, sizeof(int32_t) * d);
+  if (hv) memcpy(hv, st.V, sizeof(int32_t) * (d + 1));
+  if (hdm) memcpy(hdm, st.dmargin, sizeof(float) * d);
+  if (hvm) memcpy(hvm, st.vmargin, sizeof(float) * (d + 1));
+  if (n_accept) *n_accept = st.n_acc;
+  return st.error ? LS_E_DEVICE : LS_OK;
+}
+
+int ls_debug_capture(ls_ctx* c, float* dev_hidden) {
+  if (!c) return LS_E_ARG;
+  c->capture = dev_hidden;
+  return LS_OK;
+}
+
+const char* ls_strerror(int code) {
+  switch (code) {
+    case LS_OK: return "ok";
+    case LS_E_ARG: return "invalid argument (null pointer, unsupported shape, dtype or alignment)";
+    case LS_E_RANGE: return "value out of range (exit layer, draft length or count)";
+    case LS_E_CAPACITY: return "capacity exceeded (workspace or max_seq)";
+    case LS_E_STATE: return "call out of order (prefill -> draft -> verify)";
+    case LS_E_HIP: return "HIP runtime call failed";
+    case LS_E_DEVICE: return "device reported an error (bounded wait expired or cache capacity)";
+    default: return "unknown error";
+  }
+}
+
+void ls_destroy(ls_ctx* c) {
+  if (!c) return;
+  for (int i = 0; i < 3; ++i) (void)hipEventDestroy(c->ev[i]);
+  delete c;
+}
+
+}  // extern "C"

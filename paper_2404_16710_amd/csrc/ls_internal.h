@@ -1,0 +1,75 @@
+// Shared between the host side of the C ABI (ls_api.cpp) and the device code (ls_kernels.hip).
+#ifndef LS_INTERNAL_H_
+#define LS_INTERNAL_H_
+
+#include <stdint.h>
+#include <stddef.h>
+
+#define LS_THREADS 256          // workgroup size of the persistent kernel (4 wavefronts)
+#define LS_ROWS 16              // rows per pass (MFMA N dimension)
+#define LS_ATTN_TILE 64         // KV positions per attention work item
+#define LS_ACT_BYTES (64 * 1024) // LDS bytes for staged matmul inputs
+#define LS_MISC_BYTES 3072       // LDS bytes for state, statistics and small scratch
+#define LS_SMEM_BYTES (LS_ACT_BYTES + LS_MISC_BYTES)
+
+struct LsLayerW {
+  const void *wq, *wk, *wv, *wo, *wg, *wu, *wd, *attn_norm, *ffn_norm;
+};
+
+// Decoding state.  One copy lives in device memory (read by the host through ls_get_state /
+// ls_peek_round); every workgroup keeps an identical working copy in LDS while a program runs.
+struct LsState {
+  int32_t pos;         // KV positions that are final: prompt + emitted - 1
+  int32_t last;        // last emitted token; not yet in the cache
+  int32_t n_gen;       // tokens emitted so far
+  int32_t done;        // generation finished (max_new reached or eos emitted)
+  int32_t error;       // device-side error: 1 bounded wait expired, 2 capacity
+  int32_t n_acc;       // drafts accepted in the last round
+  int32_t draft_valid; // exit-state rows 0..draft_d hold the drafts of (draft_E, draft_d)
+  int32_t draft_E, draft_d;
+  int32_t n_emit;      // tokens the last round emitted (before the max_new cut)
+  int64_t rounds, drafted, accepted;
+  int32_t D[LS_ROWS];
+  int32_t V[LS_ROWS];
+  float dmargin[LS_ROWS];
+  float vmargin[LS_ROWS];
+};
+
+enum LsProgramKind {
+  LS_PROG_PREFILL = 0,   // tokens[0..n) through layers 0..layers_used, head on the last row
+  LS_PROG_SCORE = 1,     // same, head on every row, argmax/margin written per row
+  LS_PROG_DRAFT = 2,
+  LS_PROG_VERIFY = 3,
+  LS_PROG_GENERATE = 4   // rounds of draft+verify (d > 0) or single-token passes (d == 0)
+};
+
+struct LsKParams {
+  // model
+  int32_t L, dm, nq, nkv, hd, ffn, vocab, qd, kvd, G, max_seq;
+  float eps, attn_scale;
+  const LsLayerW *layers;
+  const void *embed, *final_norm, *lm_head;
+  const float *rope_cos, *rope_sin; // [max_seq][hd/2]
+  // workspace
+  void *kcache, *vcache;            // [L][nkv][max_seq][hd]
+  float *xbuf;                      // [16][dm]  residual rows = exit-state rows
+  float *ssq;                       // [16][dm/16] sum of squares of xbuf rows, per 16-wide tile
+  void *qbuf, *obuf, *actbuf;       // [16][qd], [16][qd], [16][ffn]
+  float *attn_part;                 // [nkv][max_tiles][64][hd+2]
+  uint32_t *attn_cnt;               // [nkv]
+  int32_t max_tiles;
+  float *cand;                      // [grid][16][4]
+  uint32_t *bar;                    // grid barrier counter
+  LsState *state;
+  float *capture;                   // [L][max_seq][dm] or null
+  // decomposition: tiles a workgroup processes at once in each stage
+  int32_t nt_qkv, nt_o, nt_gu, nt_down;
+  // program
+  int32_t kind, E, d, max_new, eos, n_tokens, layers_used;
+  const int32_t *tokens;
+  int32_t *out_tokens;
+  float *out_margin;
+  int32_t spin_limit;
+};
+
+#endif

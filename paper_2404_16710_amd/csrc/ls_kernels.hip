@@ -1,0 +1,903 @@
+// Persistent decode kernel for gfx950: every pass of greedy self-speculative decoding
+// (draft step, tail pass, verify pass, full-model step, prefill chunk) is one walk over
+//   [RMSNorm + QKV + RoPE + KV append] -> [attention] -> [O proj + residual]
+//   -> [RMSNorm + gate/up + SwiGLU] -> [down proj + residual]   per layer, then
+//   [final RMSNorm + LM head + argmax]
+// executed by one cooperative grid with grid-wide barriers between stages.  The control flow of
+// the method (Sections 4.3.1-4.3.3 and Appendix A.4 of the paper: draft d tokens with the first
+// E layers, verify 1+d rows with the remaining layers, keep the matching prefix, crop the cache)
+// runs on the device: every workgroup keeps an identical copy of the decoding state in LDS, so
+// no host round-trip is needed between rounds.
+//
+// All matrix products use one scheme for every row count m in [1,16]: weights are the MFMA A
+// operand (16 output features x K), the m activation rows are the B operand padded to 16 columns.
+// A column's result therefore does not depend on how many other rows share the pass.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <limits.h>
+#include <math.h>
+
+#include "ls_internal.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint16_t bf16_t;
+
+#define TID ((int)threadIdx.x)
+#define WAVE (TID >> 6)
+#define LANE (TID & 63)
+
+__device__ __forceinline__ float bf2f(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint32_t f2bf(float f) {  // round to nearest even
+  uint32_t u = __float_as_uint(f);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// LDS-only barrier: waits for this wave's LDS traffic, not for its global loads, so weight
+// fragments that are still in flight stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <typename T> struct TT;
+template <> struct TT<float> {
+  static constexpr int EPV = 4;  // elements per 16-byte unit
+  static __device__ __forceinline__ void unpack(const uint4& v, float* f) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ uint4 pack(const float* f) {
+    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+  }
+  static __device__ __forceinline__ float ld(const float* p) { return *p; }
+  static __device__ __forceinline__ void ld4(const float* p, float* f) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    f[0] = t.x; f[1] = t.y; f[2] = t.z; f[3] = t.w;
+  }
+  static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+  static __device__ __forceinline__ void mma(f32x4& acc, const uint4& a, const uint4& b) {
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+  }
+};
+template <> struct TT<bf16_t> {
+  static constexpr int EPV = 8;
+  static __device__ __forceinline__ void unpack(const uint4& v, float* f) {
+    f[0] = bf2f(v.x & 0xFFFFu); f[1] = bf2f(v.x >> 16); f[2] = bf2f(v.y & 0xFFFFu); f[3] = bf2f(v.y >> 16);
+    f[4] = bf2f(v.z & 0xFFFFu); f[5] = bf2f(v.z >> 16); f[6] = bf2f(v.w & 0xFFFFu); f[7] = bf2f(v.w >> 16);
+  }
+  static __device__ __forceinline__ uint4 pack(const float* f) {
+    return make_uint4(f2bf(f[0]) | (f2bf(f[1]) << 16), f2bf(f[2]) | (f2bf(f[3]) << 16),
+                      f2bf(f[4]) | (f2bf(f[5]) << 16), f2bf(f[6]) | (f2bf(f[7]) << 16));
+  }
+  static __device__ __forceinline__ float ld(const bf16_t* p) { return bf2f(*p); }
+  static __device__ __forceinline__ void ld4(const bf16_t* p, float* f) {
+    const uint2 t = *reinterpret_cast<const uint2*>(p);
+    f[0] = bf2f(t.x & 0xFFFFu); f[1] = bf2f(t.x >> 16); f[2] = bf2f(t.y & 0xFFFFu); f[3] = bf2f(t.y >> 16);
+  }
+  static __device__ __forceinline__ void st(bf16_t* p, float v) { *p = (bf16_t)f2bf(v); }
+  static __device__ __forceinline__ void mma(f32x4& acc, const uint4& a, const uint4& b) {
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+  }
+};
+
+// ------------------------------------------------------------------------------------------
+// LDS bookkeeping
+struct Best { float v1; int i1; float v2; };
+
+struct Misc {
+  LsState st;
+  int tok[LS_ROWS];
+  float rinv[LS_ROWS];
+  int r_tok[LS_ROWS];
+  float r_margin[LS_ROWS];
+  Best wb[4][LS_ROWS];
+  float redf[4][LS_ROWS];
+  unsigned epoch;
+  int flag;
+  int abort;
+};
+static_assert(sizeof(Misc) <= LS_MISC_BYTES, "Misc must fit its LDS slot");
+
+struct PassCtx {
+  int m, row0, pos0, l0, l1;
+  bool embed_src;  // rows come from the embedding table (tokens in Misc::tok) instead of xbuf
+  bool head;
+};
+
+__device__ __forceinline__ Best best_merge(const Best& a, const Best& b) {
+  const bool aw = (a.v1 > b.v1) || (a.v1 == b.v1 && a.i1 < b.i1);
+  Best r;
+  r.v1 = aw ? a.v1 : b.v1;
+  r.i1 = aw ? a.i1 : b.i1;
+  r.v2 = fmaxf(aw ? a.v2 : b.v2, aw ? b.v1 : a.v1);
+  return r;
+}
+__device__ __forceinline__ Best best_shfl_xor(const Best& a, int mask) {
+  Best b;
+  b.v1 = __shfl_xor(a.v1, mask);
+  b.i1 = __shfl_xor(a.i1, mask);
+  b.v2 = __shfl_xor(a.v2, mask);
+  return b;
+}
+
+// ------------------------------------------------------------------------------------------
+// Grid barrier.  Counter is zero at launch; barrier number e (1-based) completes when the counter
+// reaches e * gridDim.x.  The wait is bounded: when it expires the error flag is raised and every
+// workgroup leaves the kernel.
+__device__ __noinline__ bool grid_barrier(const LsKParams& P, Misc* ms) {
+  __syncthreads();
+  if (TID == 0) {
+    ms->epoch += 1;
+    const unsigned target = ms->epoch * gridDim.x;
+    __threadfence();
+    __hip_atomic_fetch_add(P.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int it = 0;
+    bool ok = true;
+    while (__hip_atomic_load(P.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      __builtin_amdgcn_s_sleep(1);
+      if (++it > P.spin_limit ||
+          ((it & 255) == 0 && __hip_atomic_load(&P.state->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+        ok = false;
+        break;
+      }
+    }
+    __threadfence();
+    if (!ok) {
+      __hip_atomic_store(&P.state->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      ms->abort = 1;
+    }
+  }
+  __syncthreads();
+  return ms->abort == 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// Matmul input rows (the MFMA B operand)
+enum { ACT_PLAIN = 0, ACT_NORM_X = 1, ACT_NORM_EMB = 2 };
+struct ActDesc {
+  int mode;
+  const void* src;   // PLAIN: T[n][ld];  NORM_X: float[n][ld];  NORM_EMB: T embed[vocab][ld]
+  int ld;
+  const void* gain;  // T[K] RMSNorm gain (NORM modes)
+};
+
+// Writes rows [0,m) x columns [k0, k0+klen) of the input into LDS as T, 16-byte units swizzled
+// by the row index so that the 16 rows of one unit column hit distinct banks.
+template <typename T>
+__device__ __forceinline__ void stage_act(const ActDesc& A, const Misc* ms, int m, int K, int k0, int klen,
+                                          int rs_units, char* act) {
+  constexpr int EPV = TT<T>::EPV;
+  const int upr = klen / EPV;
+  for (int idx = TID; idx < m * upr; idx += LS_THREADS) {
+    const int n = idx / upr, u = idx - n * upr;
+    const int k = k0 + u * EPV;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (k < K) {
+      if (A.mode == ACT_PLAIN) {
+        v = *reinterpret_cast<const uint4*>(static_cast<const T*>(A.src) + (size_t)n * A.ld + k);
+      } else {
+        float f[EPV], gn[EPV];
+        if (A.mode == ACT_NORM_X) {
+          const float* s = static_cast<const float*>(A.src) + (size_t)n * A.ld + k;
+#pragma unroll
+          for (int e = 0; e < EPV; e += 4) {
+            const float4 t = *reinterpret_cast<const float4*>(s + e);
+            f[e] = t.x; f[e + 1] = t.y; f[e + 2] = t.z; f[e + 3] = t.w;
+          }
+        } else {
+          TT<T>::unpack(*reinterpret_cast<const uint4*>(static_cast<const T*>(A.src) + (size_t)ms->tok[n] * A.ld + k), f);
+        }
+        TT<T>::unpack(*reinterpret_cast<const uint4*>(static_cast<const T*>(A.gain) + k), gn);
+        const float r = ms->rinv[n];
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) f[e] = (f[e] * r) * gn[e];
+        v = TT<T>::pack(f);
+      }
+    }
+    const int pu = (u & ~15) | ((u ^ n) & 15);
+    *reinterpret_cast<uint4*>(act + ((size_t)n * rs_units + pu) * 16) = v;
+  }
+}
+
+// One group of NT weight tiles (16 rows x K each, row-major with leading dimension K) times the
+// staged input.  The 4 waves take every 4th 256-byte block of K; DEPTH blocks per wave are kept
+// in flight.  On return the per-wave partial sums sit in LDS (`act` region) as
+// red[wave][tile][lane]; tile_sum() adds them in wave order.
+template <typename T, int NT, int DEPTH>
+__device__ __forceinline__ void gemm_group(const T* const (&wt)[NT], int K, const ActDesc& A, const Misc* ms, int m,
+                                           char* act) {
+  constexpr int KB = 256 / (int)sizeof(T);
+  constexpr int EPV = TT<T>::EPV;
+  const int lane = LANE, wave = WAVE;
+  const int r = lane & 15, g = lane >> 4;
+  const int nkb = (K + KB - 1) / KB;
+  int kcb = (LS_ACT_BYTES / (m * 256)) & ~(4 * DEPTH - 1);
+  const int nkb_up = (nkb + 4 * DEPTH - 1) & ~(4 * DEPTH - 1);
+  if (kcb > nkb_up) kcb = nkb_up;
+  const int rs_units = kcb * 16;
+
+  const T* rp[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) rp[t] = wt[t] ? wt[t] + (size_t)r * K + g * EPV : nullptr;
+
+  uint4 slot[DEPTH][NT][4];
+  auto load_slot = [&](int s, int kb) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int k = kb * KB + j * (KB / 4) + g * EPV;
+        if (rp[t] != nullptr && k < K)
+          slot[s][t][j] = *reinterpret_cast<const uint4*>(rp[t] + kb * KB + j * (KB / 4));
+        else
+          slot[s][t][j] = make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+#pragma unroll
+  for (int s = 0; s < DEPTH; ++s) load_slot(s, wave + 4 * s);
+
+  f32x4 acc[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  lds_barrier();  // the previous user of the LDS region is done with it
+  for (int c0 = 0; c0 < nkb; c0 += kcb) {
+    if (c0) lds_barrier();
+    const int cend = (c0 + kcb < nkb) ? c0 + kcb : nkb;
+    stage_act<T>(A, ms, m, K, c0 * KB, (cend - c0) * KB, rs_units, act);
+    lds_barrier();
+    for (int kb0 = c0 + wave; kb0 < cend; kb0 += 4 * DEPTH) {
+#pragma unroll
+      for (int s = 0; s < DEPTH; ++s) {
+        const int kb = kb0 + 4 * s;
+        if (kb < cend) {
+          uint4 b[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int u = (kb - c0) * 16 + j * 4 + g;
+            const int pu = (u & ~15) | ((u ^ r) & 15);
+            b[j] = (r < m) ? *reinterpret_cast<const uint4*>(act + ((size_t)r * rs_units + pu) * 16)
+                           : make_uint4(0, 0, 0, 0);
+          }
+#pragma unroll
+          for (int t = 0; t < NT; ++t) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) TT<T>::mma(acc[t], slot[s][t][j], b[j]);
+          }
+          load_slot(s, kb + 4 * DEPTH);
+        }
+      }
+    }
+  }
+  lds_barrier();
+  f32x4* red = reinterpret_cast<f32x4*>(act);
+#pragma unroll
+  for (int t = 0; t < NT; ++t) red[(wave * NT + t) * 64 + lane] = acc[t];
+  lds_barrier();
+}
+
+template <int NT>
+__device__ __forceinline__ f32x4 tile_sum(const char* act, int t) {
+  const f32x4* red = reinterpret_cast<const f32x4*>(act);
+  f32x4 s = red[(0 * NT + t) * 64 + LANE];
+#pragma unroll
+  for (int w = 1; w < 4; ++w) {
+    const f32x4 v = red[(w * NT + t) * 64 + LANE];
+    s[0] += v[0]; s[1] += v[1]; s[2] += v[2]; s[3] += v[3];
+  }
+  return s;
+}
+
+// 1/sqrt(mean(x^2) + eps) for the pass rows, into Misc::rinv.
+template <typename T>
+__device__ __noinline__ void compute_rinv(const LsKParams& P, const PassCtx& pc, bool from_embed, Misc* ms) {
+  const int lane = LANE, wave = WAVE;
+  for (int n = wave; n < pc.m; n += 4) {
+    float s = 0.f;
+    if (from_embed) {
+      const T* e = static_cast<const T*>(P.embed) + (size_t)ms->tok[n] * P.dm;
+      for (int k = lane; k < P.dm; k += 64) { const float v = TT<T>::ld(e + k); s += v * v; }
+    } else {
+      const int nt = P.dm / 16;
+      const float* q = P.ssq + (size_t)(pc.row0 + n) * nt;
+      for (int k = lane; k < nt; k += 64) s += q[k];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (lane == 0) ms->rinv[n] = 1.0f / sqrtf(s / (float)P.dm + P.eps);
+  }
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------
+// Stage A: RMSNorm + QKV projection + RoPE + KV append.  A work item is a pair of 16-row tiles:
+// for q and k the rows (j, j + hd/2) that one rotation mixes, for v two adjacent tiles.
+template <typename T, int NT>
+__device__ __noinline__ void stage_qkv(const LsKParams& P, const PassCtx& pc, int l, Misc* ms, char* act) {
+  constexpr int DEPTH = (NT == 4) ? 2 : 4;
+  constexpr int IPG = NT / 2;
+  const LsLayerW& W = P.layers[l];
+  const int hd = P.hd, dm = P.dm, half = hd / 2;
+  const int pph = hd / 32;
+  const int nq_items = P.nq * pph, nk_items = P.nkv * pph, nv_items = P.kvd / 32;
+  const int items = nq_items + nk_items + nv_items;
+  const int groups = (items + IPG - 1) / IPG;
+  const bool emb = pc.embed_src && l == pc.l0;
+  ActDesc A;
+  A.mode = emb ? ACT_NORM_EMB : ACT_NORM_X;
+  A.src = emb ? P.embed : static_cast<const void*>(P.xbuf + (size_t)pc.row0 * dm);
+  A.ld = dm;
+  A.gain = W.attn_norm;
+  const int lane = LANE, wave = WAVE, n = lane & 15, g = lane >> 4;
+  for (int grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+    const T* wt[NT];
+#pragma unroll
+    for (int u = 0; u < IPG; ++u) {
+      const int item = grp * IPG + u;
+      const T *t0 = nullptr, *t1 = nullptr;
+      if (item < nq_items) {
+        const int h = item / pph, jb = item - h * pph;
+        t0 = static_cast<const T*>(W.wq) + (size_t)(h * hd + jb * 16) * dm;
+        t1 = t0 + (size_t)half * dm;
+      } else if (item < nq_items + nk_items) {
+        const int it = item - nq_items, h = it / pph, jb = it - h * pph;
+        t0 = static_cast<const T*>(W.wk) + (size_t)(h * hd + jb * 16) * dm;
+        t1 = t0 + (size_t)half * dm;
+      } else if (item < items) {
+        const int it = item - nq_items - nk_items;
+        t0 = static_cast<const T*>(W.wv) + (size_t)(it * 32) * dm;
+        t1 = t0 + (size_t)16 * dm;
+      }
+      wt[2 * u] = t0;
+      wt[2 * u + 1] = t1;
+    }
+    gemm_group<T, NT, DEPTH>(wt, dm, A, ms, pc.m, act);
+    if (wave < IPG) {
+      const int item = grp * IPG + wave;
+      if (item < items) {
+        const f32x4 a = tile_sum<NT>(act, 2 * wave), b = tile_sum<NT>(act, 2 * wave + 1);
+        if (n < pc.m) {
+          const int pos = pc.pos0 + n;
+          if (item < nq_items + nk_items) {
+            const bool isq = item < nq_items;
+            const int it = isq ? item : item - nq_items;
+            const int h = it / pph, jb = it - h * pph;
+            T* dst = isq ? static_cast<T*>(P.qbuf) + (size_t)n * P.qd + h * hd
+                         : static_cast<T*>(P.kcache) + (((size_t)l * P.nkv + h) * P.max_seq + pos) * hd;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const int dj = jb * 16 + 4 * g + j;
+              const float c = P.rope_cos[(size_t)pos * half + dj], s = P.rope_sin[(size_t)pos * half + dj];
+              TT<T>::st(dst + dj, a[j] * c - b[j] * s);
+              TT<T>::st(dst + dj + half, b[j] * c + a[j] * s);
+            }
+          } else {
+            const int it = item - nq_items - nk_items;
+            const int row = it * 32;  // within kv_dim
+            const int h = row / hd, d0 = row - h * hd;
+            T* dst = static_cast<T*>(P.vcache) + (((size_t)l * P.nkv + h) * P.max_seq + pos) * hd + d0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              TT<T>::st(dst + 4 * g + j, a[j]);
+              TT<T>::st(dst + 16 + 4 * g + j, b[j]);
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Stage B: attention of the m query rows (x G query heads per KV head) over the shared cache.
+// A work item is (kv head, 64-position tile); the last workgroup to finish a kv head merges the
+// per-tile partial softmaxes in tile order.
+template <typename T, int HD>
+__device__ __noinline__ void stage_attn(const LsKParams& P, const PassCtx& pc, int l, Misc* ms, char* act) {
+  constexpr int TP = LS_ATTN_TILE;
+  constexpr int SEG = HD / 4;           // dims per thread in the q.k product
+  constexpr int DQ = HD / 4;            // threads across one V row (4 dims each)
+  constexpr int PARTS = LS_THREADS / DQ;
+  constexpr int KPP = TP / PARTS;       // keys per thread in the p.v product
+  constexpr int PSTRIDE = HD + 2;
+  const int tid = TID, lane = LANE, wave = WAVE;
+  const int G = P.G, nQ = pc.m * G;
+  const int tend = pc.pos0 + pc.m;  // positions in the cache after this pass
+  const int ntiles = (tend + TP - 1) / TP;
+  const int items = P.nkv * ntiles;
+  float* qs = reinterpret_cast<float*>(act);  // [16][HD]
+  float* sc = qs + 16 * HD;                    // [16][TP]
+  float* smx = sc + 16 * TP;                   // [16]
+  float* ssm = smx + 16;                       // [16]
+  float* red = ssm + 16;                       // [4][16][HD]
+  const T* kc = static_cast<const T*>(P.kcache) + (size_t)l * P.nkv * P.max_seq * HD;
+  const T* vc = static_cast<const T*>(P.vcache) + (size_t)l * P.nkv * P.max_seq * HD;
+
+  for (int item = blockIdx.x; item < items; item += gridDim.x) {
+    const int c = item / ntiles, ti = item - c * ntiles;
+    const int kp0 = ti * TP;
+    const int nvalid = (tend - kp0 < TP) ? tend - kp0 : TP;
+    // K: thread (key u, segment seg); V: thread (dim quad dq, key part)
+    const int u = tid >> 2, seg = tid & 3;
+    float kreg[SEG];
+    if (u < nvalid) {
+      const T* kp = kc + ((size_t)c * P.max_seq + kp0 + u) * HD + seg * SEG;
+#pragma unroll
+      for (int e = 0; e < SEG; e += TT<T>::EPV) TT<T>::unpack(*reinterpret_cast<const uint4*>(kp + e), &kreg[e]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < SEG; ++e) kreg[e] = 0.f;
+    }
+    const int dq = tid % DQ, part = tid / DQ;
+    float vreg[KPP][4];
+#pragma unroll
+    for (int kk = 0; kk < KPP; ++kk) {
+      const int key = part * KPP + kk;
+      if (key < nvalid) {
+        TT<T>::ld4(vc + ((size_t)c * P.max_seq + kp0 + key) * HD + dq * 4, vreg[kk]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) vreg[kk][e] = 0.f;
+      }
+    }
+    float* pout = P.attn_part + ((size_t)(c * P.max_tiles + ti) * 64) * PSTRIDE;
+
+    for (int qb = 0; qb < nQ; qb += 16) {
+      const int nqb = (nQ - qb < 16) ? nQ - qb : 16;
+      __syncthreads();
+      for (int idx = tid; idx < nqb * HD; idx += LS_THREADS) {
+        const int qi = idx / HD, dim = idx - qi * HD;
+        const int qg = qb + qi, n = qg / G, gq = qg - n * G;
+        qs[qi * HD + dim] = TT<T>::ld(static_cast<const T*>(P.qbuf) + (size_t)n * P.qd + (c * G + gq) * HD + dim);
+      }
+      __syncthreads();
+      for (int qi = 0; qi < nqb; ++qi) {
+        const float* q = qs + qi * HD + seg * SEG;
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < SEG; e += 4) {
+          const float4 qv = *reinterpret_cast<const float4*>(q + e);
+          dot += kreg[e] * qv.x; dot += kreg[e + 1] * qv.y; dot += kreg[e + 2] * qv.z; dot += kreg[e + 3] * qv.w;
+        }
+        dot += __shfl_xor(dot, 1);
+        dot += __shfl_xor(dot, 2);
+        if (seg == 0) {
+          const int qpos = pc.pos0 + (qb + qi) / G;
+          sc[qi * TP + u] = (u < nvalid && kp0 + u <= qpos) ? dot * P.attn_scale : -INFINITY;
+        }
+      }
+      __syncthreads();
+      for (int qi = wave; qi < nqb; qi += 4) {
+        const float s = sc[qi * TP + lane];
+        float mx = s;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        const float p = (s == -INFINITY) ? 0.f : expf(s - mx);
+        float sum = p;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        sc[qi * TP + lane] = p;
+        if (lane == 0) { smx[qi] = mx; ssm[qi] = sum; }
+      }
+      __syncthreads();
+      for (int qi = 0; qi < nqb; ++qi) {
+        float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KPP; ++kk) {
+          const float p = sc[qi * TP + part * KPP + kk];
+          o0 += p * vreg[kk][0]; o1 += p * vreg[kk][1]; o2 += p * vreg[kk][2]; o3 += p * vreg[kk][3];
+        }
+#pragma unroll
+        for (int o = DQ; o < 64; o <<= 1) {
+          o0 += __shfl_xor(o0, o); o1 += __shfl_xor(o1, o); o2 += __shfl_xor(o2, o); o3 += __shfl_xor(o3, o);
+        }
+        if (lane < DQ) *reinterpret_cast<float4*>(red + (wave * 16 + qi) * HD + lane * 4) = make_float4(o0, o1, o2, o3);
+      }
+      __syncthreads();
+      for (int idx = tid; idx < nqb * HD; idx += LS_THREADS) {
+        const int qi = idx / HD, dim = idx - qi * HD;
+        const float o = ((red[(0 * 16 + qi) * HD + dim] + red[(1 * 16 + qi) * HD + dim]) + red[(2 * 16 + qi) * HD + dim]) +
+                        red[(3 * 16 + qi) * HD + dim];
+        float* dst = pout + (size_t)(qb + qi) * PSTRIDE;
+        dst[dim] = o;
+        if (dim == 0) { dst[HD] = smx[qi]; dst[HD + 1] = ssm[qi]; }
+      }
+    }
+    // last arriver of this kv head merges the tiles
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+      const unsigned old = __hip_atomic_fetch_add(P.attn_cnt + c, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+      ms->flag = (old == (unsigned)(ntiles - 1));
+    }
+    __syncthreads();
+    if (ms->flag) {
+      __threadfence();
+      const float* pin = P.attn_part + ((size_t)(c * P.max_tiles) * 64) * PSTRIDE;
+      for (int idx = tid; idx < nQ * HD; idx += LS_THREADS) {
+        const int qg = idx / HD, dim = idx - qg * HD;
+        float M = -INFINITY;
+        for (int t = 0; t < ntiles; ++t) M = fmaxf(M, pin[((size_t)t * 64 + qg) * PSTRIDE + HD]);
+        float num = 0.f, den = 0.f;
+        for (int t = 0; t < ntiles; ++t) {
+          const float* pp = pin + ((size_t)t * 64 + qg) * PSTRIDE;
+          const float w = (pp[HD] == -INFINITY) ? 0.f : expf(pp[HD] - M);
+          num += w * pp[dim];
+          den += w * pp[HD + 1];
+        }
+        const int n = qg / G, gq = qg - n * G;
+        TT<T>::st(static_cast<T*>(P.obuf) + (size_t)n * P.qd + (c * G + gq) * HD + dim, num / den);
+      }
+      if (tid == 0) __hip_atomic_store(P.attn_cnt + c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Stages C and E: x += W * in  (O projection of the attention output; down projection of the
+// SwiGLU output), plus the per-tile sums of squares the next RMSNorm needs.
+template <typename T, int NT>
+__device__ __noinline__ void stage_resid(const LsKParams& P, const PassCtx& pc, int l, bool is_down, Misc* ms, char* act) {
+  constexpr int DEPTH = (NT == 4) ? 2 : 4;
+  const LsLayerW& W = P.layers[l];
+  const int dm = P.dm;
+  const int K = is_down ? P.ffn : P.qd;
+  const T* wmat = static_cast<const T*>(is_down ? W.wd : W.wo);
+  const int tiles = dm / 16;
+  const int groups = (tiles + NT - 1) / NT;
+  ActDesc A;
+  A.mode = ACT_PLAIN;
+  A.src = is_down ? P.actbuf : P.obuf;
+  A.ld = K;
+  A.gain = nullptr;
+  const bool emb = !is_down && pc.embed_src && l == pc.l0;  // residual comes from the embedding row
+  const int lane = LANE, wave = WAVE, n = lane & 15, g = lane >> 4;
+  for (int grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+    const T* wt[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int tile = grp * NT + t;
+      wt[t] = tile < tiles ? wmat + (size_t)tile * 16 * K : nullptr;
+    }
+    gemm_group<T, NT, DEPTH>(wt, K, A, ms, pc.m, act);
+    for (int t = wave; t < NT; t += 4) {
+      const int tile = grp * NT + t;
+      if (tile >= tiles) continue;
+      const f32x4 v = tile_sum<NT>(act, t);
+      const int row = tile * 16 + 4 * g;
+      float nx[4] = {0.f, 0.f, 0.f, 0.f};
+      if (n < pc.m) {
+        float* xr = P.xbuf + (size_t)(pc.row0 + n) * dm + row;
+        if (emb) {
+          const T* e = static_cast<const T*>(P.embed) + (size_t)ms->tok[n] * dm + row;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) nx[j] = TT<T>::ld(e + j) + v[j];
+        } else {
+          const float4 o = *reinterpret_cast<const float4*>(xr);
+          nx[0] = o.x + v[0]; nx[1] = o.y + v[1]; nx[2] = o.z + v[2]; nx[3] = o.w + v[3];
+        }
+        *reinterpret_cast<float4*>(xr) = make_float4(nx[0], nx[1], nx[2], nx[3]);
+        if (is_down && P.capture != nullptr)
+          *reinterpret_cast<float4*>(P.capture + ((size_t)l * P.max_seq + pc.pos0 + n) * dm + row) =
+              make_float4(nx[0], nx[1], nx[2], nx[3]);
+      }
+      float s = nx[0] * nx[0] + nx[1] * nx[1] + nx[2] * nx[2] + nx[3] * nx[3];
+      s += __shfl_xor(s, 16);
+      s += __shfl_xor(s, 32);
+      if (g == 0 && n < pc.m) P.ssq[(size_t)(pc.row0 + n) * tiles + tile] = s;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Stage D: RMSNorm + gate/up projection + SwiGLU.  A work item pairs the gate tile and the up
+// tile of the same 16 features.
+template <typename T, int NT>
+__device__ __noinline__ void stage_gu(const LsKParams& P, const PassCtx& pc, int l, Misc* ms, char* act) {
+  constexpr int DEPTH = (NT == 4) ? 2 : 4;
+  constexpr int IPG = NT / 2;
+  const LsLayerW& W = P.layers[l];
+  const int dm = P.dm;
+  const int items = P.ffn / 16;
+  const int groups = (items + IPG - 1) / IPG;
+  ActDesc A;
+  A.mode = ACT_NORM_X;
+  A.src = P.xbuf + (size_t)pc.row0 * dm;
+  A.ld = dm;
+  A.gain = W.ffn_norm;
+  const int lane = LANE, wave = WAVE, n = lane & 15, g = lane >> 4;
+  for (int grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+    const T* wt[NT];
+#pragma unroll
+    for (int u = 0; u < IPG; ++u) {
+      const int item = grp * IPG + u;
+      wt[2 * u] = item < items ? static_cast<const T*>(W.wg) + (size_t)item * 16 * dm : nullptr;
+      wt[2 * u + 1] = item < items ? static_cast<const T*>(W.wu) + (size_t)item * 16 * dm : nullptr;
+    }
+    gemm_group<T, NT, DEPTH>(wt, dm, A, ms, pc.m, act);
+    if (wave < IPG) {
+      const int item = grp * IPG + wave;
+      if (item < items && n < pc.m) {
+        const f32x4 gt = tile_sum<NT>(act, 2 * wave), up = tile_sum<NT>(act, 2 * wave + 1);
+        T* dst = static_cast<T*>(P.actbuf) + (size_t)n * P.ffn + item * 16 + 4 * g;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float z = gt[j];
+          TT<T>::st(dst + j, (z / (1.0f + expf(-z))) * up[j]);
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Head: final RMSNorm + LM head + per-row argmax (highest value, lowest index on ties) with the
+// runner-up value kept for the margin.  Each workgroup writes one candidate per row.
+template <typename T>
+__device__ __noinline__ void stage_head(const LsKParams& P, const PassCtx& pc, Misc* ms, char* act) {
+  constexpr int NT = 4, DEPTH = 2;
+  const int dm = P.dm;
+  const int tiles = P.vocab / 16;
+  const int groups = (tiles + NT - 1) / NT;
+  ActDesc A;
+  A.mode = ACT_NORM_X;
+  A.src = P.xbuf + (size_t)pc.row0 * dm;
+  A.ld = dm;
+  A.gain = P.final_norm;
+  const int lane = LANE, wave = WAVE, n = lane & 15, g = lane >> 4;
+  Best best;
+  best.v1 = -INFINITY; best.i1 = INT_MAX; best.v2 = -INFINITY;
+  for (int grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+    const T* wt[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int tile = grp * NT + t;
+      wt[t] = tile < tiles ? static_cast<const T*>(P.lm_head) + (size_t)tile * 16 * dm : nullptr;
+    }
+    gemm_group<T, NT, DEPTH>(wt, dm, A, ms, pc.m, act);
+    const int tile = grp * NT + wave;
+    if (tile < tiles) {
+      const f32x4 v = tile_sum<NT>(act, wave);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        Best c;
+        c.v1 = v[j]; c.i1 = tile * 16 + 4 * g + j; c.v2 = -INFINITY;
+        best = best_merge(best, c);
+      }
+    }
+  }
+  best = best_merge(best, best_shfl_xor(best, 16));
+  best = best_merge(best, best_shfl_xor(best, 32));
+  if (g == 0) ms->wb[wave][n] = best;
+  __syncthreads();
+  if (TID < LS_ROWS) {
+    Best b = ms->wb[0][TID];
+    b = best_merge(b, ms->wb[1][TID]);
+    b = best_merge(b, ms->wb[2][TID]);
+    b = best_merge(b, ms->wb[3][TID]);
+    *reinterpret_cast<float4*>(P.cand + ((size_t)blockIdx.x * LS_ROWS + TID) * 4) =
+        make_float4(b.v1, __int_as_float(b.i1), b.v2, 0.f);
+  }
+}
+
+// After the barrier that follows the head stage: every workgroup merges all candidates.
+__device__ __noinline__ void reduce_cands(const LsKParams& P, const PassCtx& pc, Misc* ms) {
+  const int lane = LANE, wave = WAVE;
+  for (int n = 0; n < pc.m; ++n) {
+    Best b;
+    b.v1 = -INFINITY; b.i1 = INT_MAX; b.v2 = -INFINITY;
+    for (int w = TID; w < (int)gridDim.x; w += LS_THREADS) {
+      const float4 c = *reinterpret_cast<const float4*>(P.cand + ((size_t)w * LS_ROWS + n) * 4);
+      Best cb;
+      cb.v1 = c.x; cb.i1 = __float_as_int(c.y); cb.v2 = c.z;
+      b = best_merge(b, cb);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) b = best_merge(b, best_shfl_xor(b, o));
+    if (lane == 0) ms->wb[wave][n] = b;
+  }
+  __syncthreads();
+  if (TID < pc.m) {
+    Best b = ms->wb[0][TID];
+    b = best_merge(b, ms->wb[1][TID]);
+    b = best_merge(b, ms->wb[2][TID]);
+    b = best_merge(b, ms->wb[3][TID]);
+    ms->r_tok[TID] = b.i1;
+    ms->r_margin[TID] = b.v1 - b.v2;
+  }
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__device__ bool run_pass(const LsKParams& P, const PassCtx& pc, Misc* ms, char* act) {
+  for (int l = pc.l0; l < pc.l1; ++l) {
+    compute_rinv<T>(P, pc, pc.embed_src && l == pc.l0, ms);
+    if (P.nt_qkv == 4) stage_qkv<T, 4>(P, pc, l, ms, act); else stage_qkv<T, 2>(P, pc, l, ms, act);
+    if (!grid_barrier(P, ms)) return false;
+    if (P.hd == 128) stage_attn<T, 128>(P, pc, l, ms, act); else stage_attn<T, 64>(P, pc, l, ms, act);
+    if (!grid_barrier(P, ms)) return false;
+    if (P.nt_o == 4) stage_resid<T, 4>(P, pc, l, false, ms, act);
+    else if (P.nt_o == 2) stage_resid<T, 2>(P, pc, l, false, ms, act);
+    else stage_resid<T, 1>(P, pc, l, false, ms, act);
+    if (!grid_barrier(P, ms)) return false;
+    compute_rinv<T>(P, pc, false, ms);
+    if (P.nt_gu == 4) stage_gu<T, 4>(P, pc, l, ms, act); else stage_gu<T, 2>(P, pc, l, ms, act);
+    if (!grid_barrier(P, ms)) return false;
+    if (P.nt_down == 4) stage_resid<T, 4>(P, pc, l, true, ms, act);
+    else if (P.nt_down == 2) stage_resid<T, 2>(P, pc, l, true, ms, act);
+    else stage_resid<T, 1>(P, pc, l, true, ms, act);
+    if (!grid_barrier(P, ms)) return false;
+  }
+  if (pc.head) {
+    compute_rinv<T>(P, pc, false, ms);
+    stage_head<T>(P, pc, ms, act);
+    if (!grid_barrier(P, ms)) return false;
+    reduce_cands(P, pc, ms);
+  }
+  return true;
+}
+
+__device__ __forceinline__ int clamp_tok(int t, int vocab) { return t < 0 ? 0 : (t >= vocab ? vocab - 1 : t); }
+
+// Self-drafting (Section 4.3.1) followed by the early-layer pass for the last draft.
+template <typename T>
+__device__ bool do_draft(const LsKParams& P, int E, int d, Misc* ms, char* act) {
+  PassCtx pc;
+  pc.m = 1; pc.l0 = 0; pc.l1 = E; pc.embed_src = true;
+  for (int i = 0; i <= d; ++i) {
+    if (TID == 0) ms->tok[0] = clamp_tok(i == 0 ? ms->st.last : ms->st.D[i - 1], P.vocab);
+    __syncthreads();
+    pc.row0 = i; pc.pos0 = ms->st.pos + i; pc.head = i < d;
+    if (!run_pass<T>(P, pc, ms, act)) return false;
+    if (i < d && TID == 0) { ms->st.D[i] = ms->r_tok[0]; ms->st.dmargin[i] = ms->r_margin[0]; }
+    __syncthreads();
+  }
+  if (TID == 0) { ms->st.draft_valid = 1; ms->st.draft_E = E; ms->st.draft_d = d; }
+  __syncthreads();
+  return true;
+}
+
+// Self-verification (Section 4.3.2), acceptance and cache crop (Appendix A.4).
+template <typename T>
+__device__ bool do_verify(const LsKParams& P, int E, int d, Misc* ms, char* act) {
+  PassCtx pc;
+  pc.m = d + 1; pc.row0 = 0; pc.pos0 = ms->st.pos; pc.l0 = E; pc.l1 = P.L; pc.embed_src = false; pc.head = true;
+  if (!run_pass<T>(P, pc, ms, act)) return false;
+  if (TID == 0) {
+    LsState& st = ms->st;
+    for (int i = 0; i <= d; ++i) { st.V[i] = ms->r_tok[i]; st.vmargin[i] = ms->r_margin[i]; }
+    int n = 0;
+    while (n < d && st.D[n] == st.V[n]) ++n;
+    st.n_acc = n;
+    st.n_emit = n + 1;
+    int used = 0;
+    for (int i = 0; i <= n; ++i) {
+      const int tok = (i < n) ? st.D[i] : st.V[n];
+      if (st.n_gen + i >= P.max_new) break;
+      if (P.out_tokens != nullptr && blockIdx.x == 0) P.out_tokens[st.n_gen + i] = tok;
+      used = i + 1;
+      if (tok == P.eos) { st.done = 1; break; }
+    }
+    st.pos += n + 1;
+    st.last = st.V[n];
+    st.n_gen += used;
+    st.rounds += 1;
+    st.drafted += d;
+    st.accepted += n;
+    st.draft_valid = 0;
+    if (st.n_gen >= P.max_new) st.done = 1;
+  }
+  __syncthreads();
+  return true;
+}
+
+template <typename T>
+__global__ __launch_bounds__(LS_THREADS, 2) void ls_mega(const LsKParams P) {
+  extern __shared__ __align__(16) char smem[];
+  char* act = smem;
+  Misc* ms = reinterpret_cast<Misc*>(smem + LS_ACT_BYTES);
+  if (TID == 0) {
+    ms->st = *P.state;
+    ms->epoch = 0;
+    ms->abort = 0;
+    ms->flag = 0;
+  }
+  __syncthreads();
+  bool ok = true;
+
+  if (P.kind == LS_PROG_PREFILL || P.kind == LS_PROG_SCORE) {
+    const int n = P.n_tokens;
+    for (int c0 = 0; c0 < n && ok; c0 += LS_ROWS) {
+      PassCtx pc;
+      pc.m = (n - c0 < LS_ROWS) ? n - c0 : LS_ROWS;
+      pc.row0 = 0; pc.pos0 = c0; pc.l0 = 0; pc.l1 = P.layers_used; pc.embed_src = true;
+      pc.head = (P.kind == LS_PROG_SCORE) || (c0 + LS_ROWS >= n);
+      if (TID < pc.m) ms->tok[TID] = clamp_tok(P.tokens[c0 + TID], P.vocab);
+      __syncthreads();
+      ok = run_pass<T>(P, pc, ms, act);
+      if (!ok) break;
+      if (P.kind == LS_PROG_SCORE && blockIdx.x == 0 && TID < pc.m) {
+        P.out_tokens[c0 + TID] = ms->r_tok[TID];
+        if (P.out_margin != nullptr) P.out_margin[c0 + TID] = ms->r_margin[TID];
+      }
+      if (c0 + LS_ROWS >= n && TID == 0) {
+        LsState& st = ms->st;
+        const int keep_err = st.error;
+        st = LsState{};
+        st.error = keep_err;
+        if (P.kind == LS_PROG_PREFILL) {
+          st.pos = n; st.last = ms->r_tok[pc.m - 1]; st.n_gen = 1;
+          st.vmargin[0] = ms->r_margin[pc.m - 1];
+          if (P.out_tokens != nullptr && blockIdx.x == 0) P.out_tokens[0] = st.last;
+          if (st.last == P.eos || P.max_new <= 1) st.done = 1;
+        }
+      }
+      __syncthreads();
+    }
+  } else if (P.kind == LS_PROG_DRAFT) {
+    if (ms->st.pos + P.d + 1 > P.max_seq) {
+      if (TID == 0) ms->st.error = 2;
+      __syncthreads();
+    } else {
+      ok = do_draft<T>(P, P.E, P.d, ms, act);
+    }
+  } else if (P.kind == LS_PROG_VERIFY) {
+    if (ms->st.draft_valid && ms->st.draft_E == P.E && ms->st.draft_d == P.d) ok = do_verify<T>(P, P.E, P.d, ms, act);
+  } else if (P.kind == LS_PROG_GENERATE) {
+    while (ok && !ms->st.done && ms->st.n_gen < P.max_new) {
+      if (ms->st.pos + P.d + 1 > P.max_seq) {
+        if (TID == 0) { ms->st.error = 2; ms->st.done = 1; }
+        __syncthreads();
+        break;
+      }
+      if (P.d > 0) {
+        ok = do_draft<T>(P, P.E, P.d, ms, act);
+        if (ok) ok = do_verify<T>(P, P.E, P.d, ms, act);
+      } else {
+        PassCtx pc;
+        pc.m = 1; pc.row0 = 0; pc.pos0 = ms->st.pos; pc.l0 = 0; pc.l1 = P.layers_used; pc.embed_src = true; pc.head = true;
+        if (TID == 0) ms->tok[0] = clamp_tok(ms->st.last, P.vocab);
+        __syncthreads();
+        ok = run_pass<T>(P, pc, ms, act);
+        if (ok && TID == 0) {
+          LsState& st = ms->st;
+          const int tok = ms->r_tok[0];
+          if (P.out_tokens != nullptr && blockIdx.x == 0) P.out_tokens[st.n_gen] = tok;
+          st.vmargin[0] = ms->r_margin[0];
+          st.pos += 1; st.last = tok; st.n_gen += 1;
+          if (tok == P.eos || st.n_gen >= P.max_new) st.done = 1;
+        }
+        __syncthreads();
+      }
+    }
+  }
+  if (ok && blockIdx.x == 0 && TID == 0) {
+    const int dev_err = P.state->error;
+    LsState out = ms->st;
+    if (dev_err != 0 && out.error == 0) out.error = dev_err;
+    *P.state = out;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid, hipStream_t stream) {
+  void* args[1] = {const_cast<LsKParams*>(p)};
+  const void* fn = dtype_is_bf16 ? reinterpret_cast<const void*>(&ls_mega<bf16_t>)
+                                 : reinterpret_cast<const void*>(&ls_mega<float>);
+  hipError_t e = hipLaunchCooperativeKernel(fn, dim3(grid), dim3(LS_THREADS), args, LS_SMEM_BYTES, stream);
+  return e == hipSuccess ? 0 : (int)e;
+}
+
+extern "C" int ls_kernel_setup(int dtype_is_bf16, int* max_blocks_per_cu) {
+  const void* fn = dtype_is_bf16 ? reinterpret_cast<const void*>(&ls_mega<bf16_t>)
+                                 : reinterpret_cast<const void*>(&ls_mega<float>);
+  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LS_SMEM_BYTES);
+  if (e != hipSuccess) return (int)e;
+  int nb = 0;
+  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, LS_THREADS, LS_SMEM_BYTES);
+  if (e != hipSuccess) return (int)e;
+  *max_blocks_per_cu = nb;
+  return 0;
+}

@@ -1,0 +1,194 @@
+"""GPU parity on small models: the HIP path through the C ABI against the CPU oracle, element by
+element (token ids, per-round drafts / verified tokens / accepted counts, per-layer hidden
+states).  Tolerances: ids identical except where the oracle's top-1/top-2 logit margin is below
+1e-2 (flagged, excluded); hidden states within 1e-4 (fp32) or 2e-2 (bf16) of max|ref| per row."""
+import numpy as np
+import pytest
+
+import oracle as O
+import workloads as W
+from parity_util import same_until_near_tie, rel_err_rows, NEAR_TIE
+
+pytestmark = pytest.mark.gpu
+
+
+def _tiny(dtype="f32", **kw):
+    base = dict(name="tiny", n_layers=4, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, ffn_dim=688,
+                vocab=1024, rope_base=10000.0, rms_eps=1e-5, dtype=dtype)
+    base.update(kw)
+    return W.ModelConfig(**base)
+
+
+def _setup(w, max_seq=None, emulate=None):
+    from paper_2404_16710_amd import LsModel
+    ws, prompt = W.make_weights(w), W.make_prompt(w)
+    emu = (w.model.dtype == "bf16") if emulate is None else emulate
+    om = O.OracleModel(w.model, ws, np.float32, emulate_bf16_act=emu)
+    gm = LsModel(w.model, ws, max_seq=max_seq or (w.n_prompt + w.n_new + 16 + 1))
+    return ws, prompt, om, gm
+
+
+CASES = {
+    "c1": W.get_workload("c1"),
+    "c1-gains": W.get_workload("c1").with_(gain_jitter=0.2, weight_seed=3),
+    "c1-bf16": W.get_workload("c1").with_(model=_tiny("bf16", name="c1-bf16"), gain_jitter=0.1),
+    "gqa-hd128-bf16": W.Workload(_tiny("bf16", name="gqa", n_q_heads=4, n_kv_heads=1, head_dim=128, d_model=384,
+                                       ffn_dim=1040, vocab=2064, n_layers=3),
+                                 exit_layer=1, draft_len=5, n_prompt=70, n_new=40, resid_scale=0.1, gain_jitter=0.1),
+    "gqa2-f32": W.Workload(_tiny("f32", name="gqa2", n_q_heads=8, n_kv_heads=4, head_dim=64, d_model=320,
+                                 ffn_dim=848, vocab=1040, n_layers=3, rope_base=500000.0),
+                           exit_layer=2, draft_len=3, n_prompt=19, n_new=30, resid_scale=0.05, gain_jitter=0.1),
+}
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_generate_matches_oracle_and_full_greedy(name):
+    w = CASES[name]
+    ws, prompt, om, gm = _setup(w)
+    ref = O.self_speculative(om, prompt, w.n_new, w.exit_layer, w.draft_len)
+    toks, st = gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
+    ar, st_ar = gm.generate(prompt, w.n_new, 0, 0)
+    assert len(toks) == len(ar) == w.n_new and st.generated == w.n_new
+    n = same_until_near_tie(toks, ref.tokens, ref.margins)
+    same_until_near_tie(ar, ref.tokens, ref.margins)
+    assert toks == ar                       # the GPU path is lossless against its own full greedy
+    assert st_ar.rounds == 0 and st.drafted == st.rounds * w.draft_len
+    if n == w.n_new:                        # no divergence: the round statistics must agree too
+        assert (st.rounds, st.accepted) == (len(ref.rounds), ref.accepted)
+    gm.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "c1-bf16", "gqa-hd128-bf16"])
+def test_teacher_forced_scores_match_oracle(name):
+    """Full-model argmax of every row of prompt+output, given the oracle's own sequence: covers every
+    position regardless of where a free-running comparison would diverge."""
+    w = CASES[name]
+    ws, prompt, om, gm = _setup(w)
+    ref = O.greedy_full(om, prompt, w.n_new, want_hidden=True)
+    seq = list(prompt) + ref.tokens[:-1]
+    cap = gm.debug_capture(True)
+    am, mg = gm.score(seq)
+    P = len(prompt)
+    bad = [i for i in range(w.n_new) if am[P - 1 + i] != ref.tokens[i] and ref.margins[i] >= NEAR_TIE]
+    assert not bad, bad
+    firm = [i for i in range(w.n_new) if ref.margins[i] >= NEAR_TIE]
+    assert len(firm) > w.n_new // 2
+    np.testing.assert_allclose(mg[P - 1:][firm], np.array(ref.margins)[firm], rtol=0.05, atol=2e-3)
+    hid = cap.cpu().numpy()[:, :len(seq), :]                       # x_1..x_L
+    tol = 2e-2 if w.model.dtype == "bf16" else 1e-4
+    for l in range(w.model.n_layers):
+        assert rel_err_rows(hid[l], ref.hidden[l + 1]) < tol, l
+    gm.close()
+
+
+@pytest.mark.parametrize("name,E,d", [("c1", 2, 4), ("c1", 1, 1), ("c1", 4, 15), ("c1", 3, 7),
+                                      ("c1-bf16", 2, 6), ("gqa-hd128-bf16", 2, 12)])
+def test_rounds_replayed_from_oracle_state(name, E, d):
+    """ls_prefill / ls_draft / ls_verify from the oracle's state at each round: drafts, verified
+    tokens, accepted count and the new state must be the oracle's (near-ties excluded)."""
+    w = CASES[name]
+    ws, prompt, om, gm = _setup(w)
+    if E != w.exit_layer:
+        ws = W.make_weights(w, exit_layer=E)
+        om = O.OracleModel(w.model, ws, np.float32, emulate_bf16_act=(w.model.dtype == "bf16"))
+        from paper_2404_16710_amd import LsModel
+        gm.close()
+        gm = LsModel(w.model, ws, max_seq=w.n_prompt + w.n_new + 17)
+    ref = O.self_speculative(om, prompt, min(w.n_new, 40), E, d)
+    checked = 0
+    for r in ref.rounds[:6]:
+        seq = list(prompt) + ref.tokens[: r.pos - len(prompt)]
+        gm.prefill(seq)
+        pos, last, n_gen = gm.get_state()
+        assert pos == r.pos and n_gen == 1
+        if last != r.last:
+            continue                                              # prefill token sat on a near-tie
+        gm.draft(E, d)
+        gm.verify(E, d)
+        D, V, dmg, vmg, n_acc = gm.peek_round(d)
+        # draft i is comparable while every earlier draft margin was firm; verified row i needs the
+        # same inputs (last, D_0..D_{i-1}) and a firm margin of its own
+        kd = next((i for i, g in enumerate(r.draft_margins) if g < NEAR_TIE), d)
+        assert D[:kd] == r.draft[:kd]
+        checked += kd
+        for i in range(min(kd, d) + 1):
+            if r.verify_margins[i] >= NEAR_TIE and D[:i] == r.draft[:i]:
+                assert V[i] == r.verify[i], (i, V, r.verify)
+                checked += 1
+        if kd == d and all(g >= NEAR_TIE for g in r.verify_margins):
+            assert V == r.verify and n_acc == r.n_accept
+            pos2, last2, n_gen2 = gm.get_state()
+            assert (pos2, last2, n_gen2) == (r.pos + r.n_accept + 1, r.verify[r.n_accept], 1 + r.n_accept + 1)
+    assert checked >= 1
+    gm.close()
+
+
+def test_exit_at_last_layer_accepts_everything_on_gpu():
+    w = CASES["c1"]
+    ws, prompt, om, gm = _setup(w)
+    L = w.model.n_layers
+    toks, st = gm.generate(prompt, 41, L, 5)
+    assert st.accepted == st.drafted and st.rounds == (41 - 1 + 5) // 6
+    ar, _ = gm.generate(prompt, 41, 0, 0)
+    assert toks == ar
+    gm.close()
+
+
+def test_early_exit_generation_matches_oracle():
+    w = CASES["c1"]
+    ws, prompt, om, gm = _setup(w)
+    ref = O.early_exit_greedy(om, prompt, 32, 2)
+    toks, _ = gm.generate_early_exit(prompt, 32, 2)
+    same_until_near_tie(toks, ref.tokens, ref.margins)
+    gm.close()
+
+
+@pytest.mark.parametrize("n_prompt", [1, 15, 16, 17, 33])
+def test_ragged_prompt_lengths(n_prompt):
+    w = CASES["c1"].with_(n_prompt=n_prompt, n_new=12)
+    ws, prompt, om, gm = _setup(w)
+    ref = O.greedy_full(om, prompt, 12)
+    toks, _ = gm.generate(prompt, 12, 2, 4)
+    same_until_near_tie(toks, ref.tokens, ref.margins)
+    gm.close()
+
+
+def test_eos_stops_generation_and_output_tail_is_padded():
+    w = CASES["c1"]
+    ws, prompt, om, gm = _setup(w)
+    full, _ = gm.generate(prompt, 30, 0, 0)
+    eos = full[7]
+    first = full.index(eos)
+    toks, st = gm.generate(prompt, 30, 2, 4, eos_id=eos)
+    assert toks == full[: first + 1] and st.generated == first + 1
+    gm.close()
+
+
+def test_argument_errors_leave_no_work():
+    from paper_2404_16710_amd import LsError
+    w = CASES["c1"]
+    ws, prompt, om, gm = _setup(w, max_seq=64)
+    with pytest.raises(LsError) as e:
+        gm.draft(2, 4)
+    assert e.value.code == -4                                      # draft before prefill
+    gm.prefill(prompt)
+    with pytest.raises(LsError) as e:
+        gm.verify(2, 4)
+    assert e.value.code == -4                                      # verify without draft
+    with pytest.raises(LsError) as e:
+        gm.draft(0, 4)
+    assert e.value.code == -2
+    with pytest.raises(LsError) as e:
+        gm.draft(5, 4)
+    assert e.value.code == -2
+    with pytest.raises(LsError) as e:
+        gm.generate(prompt, 64, 2, 4)
+    assert e.value.code == -3                                      # would not fit max_seq
+    gm.draft(2, 4)
+    with pytest.raises(LsError) as e:
+        gm.verify(2, 3)                                            # d differs from the draft
+    assert e.value.code == -4
+    gm.verify(2, 4)
+    pos, last, n_gen = gm.get_state()
+    assert n_gen >= 2 and pos == len(prompt) + n_gen - 1
+    gm.close()
