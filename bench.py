@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: greedy self-speculative decoding at batch 1 on one MI355X.
+
+One "step" is one whole job of the workload: prefill of the prompt, then draft/verify rounds
+until n_new tokens exist (ls_generate), with weights and prompt already resident in HBM.
+After the timed steps the same kernels run full-model greedy decoding (d = 0) on the same
+weights for the speed-up, and the CPU oracle is timed on a bounded sample of the same job.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+
+def decode_bytes_selfspec(m, P, E, d, rounds, pos_final):
+    """Algorithmic bytes of the decode launch: weights read once per pass plus the KV rows each
+    pass attends to (positions interpolated linearly over the rounds)."""
+    Wl, Wh, kv = m.layer_weight_bytes(), m.head_weight_bytes(), m.kv_bytes_per_pos_layer()
+    L = m.n_layers
+    total = 0.0
+    adv = (pos_final - P) / max(rounds, 1)
+    for r in range(rounds):
+        pos = P + r * adv
+        for i in range(d):
+            total += E * Wl + Wh + E * (pos + i + 1) * kv
+        total += E * Wl + E * (pos + d + 1) * kv
+        total += (L - E) * Wl + Wh + (L - E) * (pos + d + 1) * kv
+    return total
+
+
+def decode_bytes_ar(m, P, n_new):
+    Wl, Wh, kv = m.layer_weight_bytes(), m.head_weight_bytes(), m.kv_bytes_per_pos_layer()
+    L = m.n_layers
+    return sum(L * Wl + Wh + L * (P + k) * kv for k in range(1, n_new))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="c2", help="workload: c1..c5 (default c2, the 1.5B model)")
+    ap.add_argument("--exit-layer", type=int, default=None)
+    ap.add_argument("--draft", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-new", type=int, default=24)
+    ap.add_argument("--wg-per-cu", type=int, default=0)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import workloads as W
+    from paper_2404_16710_amd import LsModel
+
+    w = W.get_workload(a.config)
+    E = a.exit_layer or w.exit_layer
+    d = a.draft if a.draft is not None else w.draft_len
+    m = w.model
+    t0 = time.time()
+    weights = W.make_weights(w, exit_layer=E, threads=min(16, len(os.sched_getaffinity(0))))
+    prompt = W.make_prompt(w)
+    t_gen = time.time() - t0
+    model = LsModel(m, weights, max_seq=w.n_prompt + w.n_new + 16 + 1)
+    if a.wg_per_cu:
+        model.set_launch(a.wg_per_cu)
+    print(f"[bench] {m.name}: weights generated in {t_gen:.1f}s, uploaded; E={E} d={d} "
+          f"P={w.n_prompt} N={w.n_new}", file=sys.stderr, flush=True)
+
+    for _ in range(a.warmup):
+        model.generate(prompt, w.n_new, E, d)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    runs = []
+    for _ in range(a.steps):
+        toks, st = model.generate(prompt, w.n_new, E, d)
+        runs.append(st)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec = t1 - t0
+    value = a.steps * w.n_new / sec
+    ms_dec = float(np.mean([r.ms_decode for r in runs]))
+    ms_pre = float(np.mean([r.ms_prefill for r in runs]))
+    st = runs[-1]
+    pos_final, _, _ = model.get_state()
+
+    # full-model greedy on the same kernels and weights (the "Autoregressive" baseline)
+    model.generate(prompt, w.n_new, 0, 0)
+    ar_runs = [model.generate(prompt, w.n_new, 0, 0) for _ in range(max(1, min(a.steps, 3)))]
+    ar_toks = ar_runs[-1][0]
+    ar_ms_dec = float(np.mean([r[1].ms_decode for r in ar_runs]))
+    ar_ms_pre = float(np.mean([r[1].ms_prefill for r in ar_runs]))
+
+    b_ss = decode_bytes_selfspec(m, w.n_prompt, E, d, st.rounds, pos_final)
+    b_ar = decode_bytes_ar(m, w.n_prompt, w.n_new)
+    ach = b_ss / (ms_dec * 1e-3) / 1e9
+    ach_ar = b_ar / (ar_ms_dec * 1e-3) / 1e9
+
+    out = {
+        "metric": "generated tokens/s at batch 1, greedy self-speculative decoding (whole job: prefill + decode)",
+        "value": round(value, 2), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(sec / a.steps * 1e3, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if m.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{a.config}: {m.name} L{m.n_layers} dm{m.d_model} ffn{m.ffn_dim} V{m.vocab}, "
+                               f"prompt {w.n_prompt}, {w.n_new} new tokens, E={E}, d={d}, batch 1",
+                   "exit_layer": E, "draft_len": d, "n_prompt": w.n_prompt, "n_new": w.n_new},
+        "selfspec": {"decode_tokens_per_s": round((w.n_new - 1) / (ms_dec * 1e-3), 2),
+                     "ms_prefill": round(ms_pre, 3), "ms_decode": round(ms_dec, 3),
+                     "acceptance": round(st.acceptance, 4), "rounds": st.rounds,
+                     "tokens_per_round": round((w.n_new - 1) / max(st.rounds, 1), 3)},
+        "full_greedy": {"tokens_per_s": round(w.n_new / ((ar_ms_pre + ar_ms_dec) * 1e-3), 2),
+                        "decode_tokens_per_s": round((w.n_new - 1) / (ar_ms_dec * 1e-3), 2),
+                        "ms_prefill": round(ar_ms_pre, 3), "ms_decode": round(ar_ms_dec, 3),
+                        "hbm_gbs": round(ach_ar, 1), "hbm_frac": round(ach_ar / HBM_PEAK_GBS, 4)},
+        "speedup_vs_full_greedy": round(ar_ms_dec / ms_dec, 3),
+        "same_ids_as_full_greedy": bool(toks == ar_toks),
+        "roofline": {"bound": "hbm", "kernel": "ls_decode_kernel (draft + tail + verify passes of all rounds)",
+                     "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                     "bytes_per_launch": int(b_ss), "ms_per_launch": round(ms_dec, 3)},
+    }
+
+    if not a.no_cpu_baseline:
+        import oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        om = O.OracleModel(m, weights, np.float32, emulate_bf16_act=(m.dtype == "bf16"))
+        n_s = min(a.cpu_sample_new, w.n_new)
+        c0 = time.perf_counter()
+        cache = om.new_cache(w.n_prompt + 2)
+        O.prefill(om, prompt, cache)
+        c_pre = time.perf_counter() - c0
+        del cache
+        c0 = time.perf_counter()
+        ref = O.self_speculative(om, prompt, n_s, E, d)
+        c_all = time.perf_counter() - c0
+        out["cpu_baseline"] = {
+            "value": round(n_s / c_all, 3), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"same weights and {w.n_prompt}-id prompt, first {n_s} of {w.n_new} new tokens "
+                      f"(prefill included, {c_pre:.1f}s of {c_all:.1f}s), E={E} d={d}, numpy float32",
+            "decode_tokens_per_s": round((n_s - 1) / max(c_all - c_pre, 1e-9), 3),
+            "acceptance": round(ref.acceptance, 4),
+            "ids_match_gpu_until_near_tie": int(next((i for i, (x, y) in enumerate(zip(toks, ref.tokens)) if x != y), n_s)),
+        }
+    model.close()
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -794,7 +794,7 @@ __device__ bool do_verify(const LsKParams& P, int E, int d, Misc* ms, char* act)
 }
 
 template <typename T>
-__global__ __launch_bounds__(LS_THREADS, 2) void ls_mega(const LsKParams P) {
+__device__ __forceinline__ void program_body(const LsKParams& P) {
   extern __shared__ __align__(16) char smem[];
   char* act = smem;
   Misc* ms = reinterpret_cast<Misc*>(smem + LS_ACT_BYTES);
@@ -881,23 +881,40 @@ __global__ __launch_bounds__(LS_THREADS, 2) void ls_mega(const LsKParams P) {
   }
 }
 
+// Two kernel symbols so that profiles separate the prompt passes from the decode rounds.
+template <typename T>
+__global__ __launch_bounds__(LS_THREADS, 2) void ls_prompt_kernel(const LsKParams P) { program_body<T>(P); }
+template <typename T>
+__global__ __launch_bounds__(LS_THREADS, 2) void ls_decode_kernel(const LsKParams P) { program_body<T>(P); }
+
 // ------------------------------------------------------------------------------------------
+static const void* kernel_for(int kind, int dtype_is_bf16) {
+  const bool prompt = kind == LS_PROG_PREFILL || kind == LS_PROG_SCORE;
+  if (dtype_is_bf16)
+    return prompt ? reinterpret_cast<const void*>(&ls_prompt_kernel<bf16_t>)
+                  : reinterpret_cast<const void*>(&ls_decode_kernel<bf16_t>);
+  return prompt ? reinterpret_cast<const void*>(&ls_prompt_kernel<float>)
+                : reinterpret_cast<const void*>(&ls_decode_kernel<float>);
+}
+
 extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid, hipStream_t stream) {
   void* args[1] = {const_cast<LsKParams*>(p)};
-  const void* fn = dtype_is_bf16 ? reinterpret_cast<const void*>(&ls_mega<bf16_t>)
-                                 : reinterpret_cast<const void*>(&ls_mega<float>);
-  hipError_t e = hipLaunchCooperativeKernel(fn, dim3(grid), dim3(LS_THREADS), args, LS_SMEM_BYTES, stream);
+  hipError_t e = hipLaunchCooperativeKernel(kernel_for(p->kind, dtype_is_bf16), dim3(grid), dim3(LS_THREADS), args,
+                                            LS_SMEM_BYTES, stream);
   return e == hipSuccess ? 0 : (int)e;
 }
 
 extern "C" int ls_kernel_setup(int dtype_is_bf16, int* max_blocks_per_cu) {
-  const void* fn = dtype_is_bf16 ? reinterpret_cast<const void*>(&ls_mega<bf16_t>)
-                                 : reinterpret_cast<const void*>(&ls_mega<float>);
-  hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LS_SMEM_BYTES);
-  if (e != hipSuccess) return (int)e;
-  int nb = 0;
-  e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, LS_THREADS, LS_SMEM_BYTES);
-  if (e != hipSuccess) return (int)e;
-  *max_blocks_per_cu = nb;
+  int nb_min = 1 << 30;
+  for (int kind : {(int)LS_PROG_PREFILL, (int)LS_PROG_GENERATE}) {
+    const void* fn = kernel_for(kind, dtype_is_bf16);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LS_SMEM_BYTES);
+    if (e != hipSuccess) return (int)e;
+    int nb = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, LS_THREADS, LS_SMEM_BYTES);
+    if (e != hipSuccess) return (int)e;
+    if (nb < nb_min) nb_min = nb;
+  }
+  *max_blocks_per_cu = nb_min;
   return 0;
 }
