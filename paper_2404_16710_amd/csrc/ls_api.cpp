@@ -62,7 +62,7 @@ Layout make_layout(const ls_config* c) {
   L.attn_part = take(sizeof(float) * c->n_kv_heads * max_tiles * 64 * (c->head_dim + 2));
   L.attn_cnt = take(sizeof(uint32_t) * c->n_kv_heads);
   L.cand = take(sizeof(float) * 4 * LS_ROWS * kMaxGrid);
-  L.bar = take(256);
+  L.bar = take(4096);
   L.state = take(sizeof(LsState));
   L.total = off;
   return L;
@@ -110,7 +110,7 @@ void set_decomposition(ls_ctx* c) {
 }
 
 int launch(ls_ctx* c, LsKParams& p, hipStream_t s) {
-  if (hipMemsetAsync(p.bar, 0, 256, s) != hipSuccess) return LS_E_HIP;
+  if (hipMemsetAsync(p.bar, 0, 4096, s) != hipSuccess) return LS_E_HIP;
   if (ls_launch_program(&p, c->cfg.dtype == LS_BF16, c->grid, s) != 0) return LS_E_HIP;
   return LS_OK;
 }

@@ -3,19 +3,27 @@
 //   [RMSNorm + QKV + RoPE + KV append] -> [attention] -> [O proj + residual]
 //   -> [RMSNorm + gate/up + SwiGLU] -> [down proj + residual]   per layer, then
 //   [final RMSNorm + LM head + argmax]
-// executed by one cooperative grid with grid-wide barriers between stages.  The control flow of
-// the method (Sections 4.3.1-4.3.3 and Appendix A.4 of the paper: draft d tokens with the first
-// E layers, verify 1+d rows with the remaining layers, keep the matching prefix, crop the cache)
-// runs on the device: every workgroup keeps an identical copy of the decoding state in LDS, so
-// no host round-trip is needed between rounds.
+// executed by one grid that stays resident, with grid-wide barriers between stages.  The control
+// flow of the method (Sections 4.3.1-4.3.3 and Appendix A.4 of the paper: draft d tokens with the
+// first E layers, verify 1+d rows with the remaining layers, keep the matching prefix, crop the
+// cache) runs on the device: every workgroup keeps an identical copy of the decoding state in LDS,
+// so no host round-trip is needed between rounds.
 //
 // All matrix products use one scheme for every row count m in [1,16]: weights are the MFMA A
 // operand (16 output features x K), the m activation rows are the B operand padded to 16 columns.
 // A column's result therefore does not depend on how many other rows share the pass.
+//
+// Memory discipline.  Weights, embeddings and the rotary table are immutable and read with plain
+// loads.  Everything a kernel writes for other workgroups (residual rows, q, attention output,
+// SwiGLU output, KV cache, partial results) is written and read with agent-scope relaxed atomic
+// accesses of 4 or 8 bytes, which go to the coherent level of the memory system directly; the grid
+// barrier then needs no cache write-back or invalidate, only "my stores have completed" before the
+// arrival and a compiler barrier around it.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <limits.h>
 #include <math.h>
+#include <stdlib.h>
 
 #include "ls_internal.h"
 
@@ -36,6 +44,35 @@ __device__ __forceinline__ uint32_t f2bf(float f) {  // round to nearest even
 // LDS-only barrier: waits for this wave's LDS traffic, not for its global loads, so weight
 // fragments that are still in flight stay in flight across it.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+// All of this wave's global stores and loads have completed.
+__device__ __forceinline__ void drain_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Coherent (agent-scope) accesses for data exchanged between workgroups.
+__device__ __forceinline__ uint64_t ldc64(const void* p) {
+  return __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t ldc32(const void* p) {
+  return __hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void stc64(void* p, uint64_t v) {
+  __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void stc32(void* p, uint32_t v) {
+  __hip_atomic_store(reinterpret_cast<uint32_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ldcf(const float* p) { return __uint_as_float(ldc32(p)); }
+__device__ __forceinline__ void stcf(float* p, float v) { stc32(p, __float_as_uint(v)); }
+__device__ __forceinline__ float2 ldcf2(const float* p) {
+  const uint64_t v = ldc64(p);
+  return make_float2(__uint_as_float((uint32_t)v), __uint_as_float((uint32_t)(v >> 32)));
+}
+__device__ __forceinline__ void stcf2(float* p, float a, float b) {
+  stc64(p, (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32));
+}
+__device__ __forceinline__ uint4 ldc128(const void* p) {
+  const uint64_t a = ldc64(p), b = ldc64(static_cast<const char*>(p) + 8);
+  return make_uint4((uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32));
+}
 
 template <typename T> struct TT;
 template <> struct TT<float> {
@@ -47,11 +84,13 @@ template <> struct TT<float> {
     return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
   }
   static __device__ __forceinline__ float ld(const float* p) { return *p; }
-  static __device__ __forceinline__ void ld4(const float* p, float* f) {
-    const float4 t = *reinterpret_cast<const float4*>(p);
-    f[0] = t.x; f[1] = t.y; f[2] = t.z; f[3] = t.w;
+  // 4 consecutive elements, coherent
+  static __device__ __forceinline__ void ldc4(const float* p, float* f) {
+    const float2 a = ldcf2(p), b = ldcf2(p + 2);
+    f[0] = a.x; f[1] = a.y; f[2] = b.x; f[3] = b.y;
   }
-  static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+  static __device__ __forceinline__ void stc4(float* p, const float* f) { stcf2(p, f[0], f[1]); stcf2(p + 2, f[2], f[3]); }
+  static __device__ __forceinline__ void stc2(float* p, float a, float b) { stcf2(p, a, b); }
   static __device__ __forceinline__ void mma(f32x4& acc, const uint4& a, const uint4& b) {
     acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
     acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
@@ -70,11 +109,15 @@ template <> struct TT<bf16_t> {
                       f2bf(f[4]) | (f2bf(f[5]) << 16), f2bf(f[6]) | (f2bf(f[7]) << 16));
   }
   static __device__ __forceinline__ float ld(const bf16_t* p) { return bf2f(*p); }
-  static __device__ __forceinline__ void ld4(const bf16_t* p, float* f) {
-    const uint2 t = *reinterpret_cast<const uint2*>(p);
-    f[0] = bf2f(t.x & 0xFFFFu); f[1] = bf2f(t.x >> 16); f[2] = bf2f(t.y & 0xFFFFu); f[3] = bf2f(t.y >> 16);
+  static __device__ __forceinline__ void ldc4(const bf16_t* p, float* f) {
+    const uint64_t t = ldc64(p);
+    const uint32_t lo = (uint32_t)t, hi = (uint32_t)(t >> 32);
+    f[0] = bf2f(lo & 0xFFFFu); f[1] = bf2f(lo >> 16); f[2] = bf2f(hi & 0xFFFFu); f[3] = bf2f(hi >> 16);
   }
-  static __device__ __forceinline__ void st(bf16_t* p, float v) { *p = (bf16_t)f2bf(v); }
+  static __device__ __forceinline__ void stc4(bf16_t* p, const float* f) {
+    stc64(p, (uint64_t)(f2bf(f[0]) | (f2bf(f[1]) << 16)) | ((uint64_t)(f2bf(f[2]) | (f2bf(f[3]) << 16)) << 32));
+  }
+  static __device__ __forceinline__ void stc2(bf16_t* p, float a, float b) { stc32(p, f2bf(a) | (f2bf(b) << 16)); }
   static __device__ __forceinline__ void mma(f32x4& acc, const uint4& a, const uint4& b) {
     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
   }
@@ -91,7 +134,6 @@ struct Misc {
   int r_tok[LS_ROWS];
   float r_margin[LS_ROWS];
   Best wb[4][LS_ROWS];
-  float redf[4][LS_ROWS];
   unsigned epoch;
   int flag;
   int abort;
@@ -121,33 +163,35 @@ __device__ __forceinline__ Best best_shfl_xor(const Best& a, int mask) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Grid barrier.  Counter is zero at launch; barrier number e (1-based) completes when the counter
-// reaches e * gridDim.x.  The wait is bounded: when it expires the error flag is raised and every
-// workgroup leaves the kernel.
-__device__ __noinline__ bool grid_barrier(const LsKParams& P, Misc* ms) {
-  __syncthreads();
+// Grid barrier, two levels: workgroups are split into 8 groups by (id mod 8); the last arriver of
+// a group bumps the grid counter, which everybody polls.  Counters are zero at launch and only
+// grow: barrier number e completes when the grid counter reaches e * groups.  The caller must
+// have drained its stores (drain_vmem) before; loads issued earlier may still be in flight.
+// The wait is bounded: when it expires the error flag is raised and every workgroup leaves.
+__device__ __forceinline__ bool grid_barrier(const LsKParams& P, Misc* ms) {
+  lds_barrier();
   if (TID == 0) {
-    ms->epoch += 1;
-    const unsigned target = ms->epoch * gridDim.x;
-    __threadfence();
-    __hip_atomic_fetch_add(P.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned epoch = ++ms->epoch;
+    const unsigned nwg = gridDim.x, wg = blockIdx.x;
+    const unsigned ngrp = nwg < 8u ? nwg : 8u;
+    const unsigned grp = wg % ngrp;
+    const unsigned gsize = (nwg - grp + ngrp - 1) / ngrp;
+    uint32_t* gcnt = P.bar + 64 * (1 + grp);
+    const unsigned old = __hip_atomic_fetch_add(gcnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == epoch * gsize - 1) __hip_atomic_fetch_add(P.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned target = epoch * ngrp;
     int it = 0;
-    bool ok = true;
     while (__hip_atomic_load(P.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
       __builtin_amdgcn_s_sleep(1);
       if (++it > P.spin_limit ||
-          ((it & 255) == 0 && __hip_atomic_load(&P.state->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-        ok = false;
+          ((it & 1023) == 0 && __hip_atomic_load(&P.state->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+        __hip_atomic_store(&P.state->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ms->abort = 1;
         break;
       }
     }
-    __threadfence();
-    if (!ok) {
-      __hip_atomic_store(&P.state->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      ms->abort = 1;
-    }
   }
-  __syncthreads();
+  lds_barrier();
   return ms->abort == 0;
 }
 
@@ -174,15 +218,15 @@ __device__ __forceinline__ void stage_act(const ActDesc& A, const Misc* ms, int 
     uint4 v = make_uint4(0, 0, 0, 0);
     if (k < K) {
       if (A.mode == ACT_PLAIN) {
-        v = *reinterpret_cast<const uint4*>(static_cast<const T*>(A.src) + (size_t)n * A.ld + k);
+        v = ldc128(static_cast<const T*>(A.src) + (size_t)n * A.ld + k);
       } else {
         float f[EPV], gn[EPV];
         if (A.mode == ACT_NORM_X) {
           const float* s = static_cast<const float*>(A.src) + (size_t)n * A.ld + k;
 #pragma unroll
-          for (int e = 0; e < EPV; e += 4) {
-            const float4 t = *reinterpret_cast<const float4*>(s + e);
-            f[e] = t.x; f[e + 1] = t.y; f[e + 2] = t.z; f[e + 3] = t.w;
+          for (int e = 0; e < EPV; e += 2) {
+            const float2 t = ldcf2(s + e);
+            f[e] = t.x; f[e + 1] = t.y;
           }
         } else {
           TT<T>::unpack(*reinterpret_cast<const uint4*>(static_cast<const T*>(A.src) + (size_t)ms->tok[n] * A.ld + k), f);
@@ -199,29 +243,21 @@ __device__ __forceinline__ void stage_act(const ActDesc& A, const Misc* ms, int 
   }
 }
 
-// One group of NT weight tiles (16 rows x K each, row-major with leading dimension K) times the
-// staged input.  The 4 waves take every 4th 256-byte block of K; DEPTH blocks per wave are kept
-// in flight.  On return the per-wave partial sums sit in LDS (`act` region) as
-// red[wave][tile][lane]; tile_sum() adds them in wave order.
+// NT weight tiles (16 rows x K each, row-major with leading dimension K) times the staged input.
+// The 4 waves take every 4th 256-byte block of K; DEPTH blocks per wave are kept in flight.
+// begin() issues the first loads (it may be called before a grid barrier: weights do not depend
+// on other workgroups); run() stages the input, multiplies, and leaves the per-wave partial sums
+// in LDS (`act` region) as red[wave][tile][lane]; tile_sum() adds them in wave order.
 template <typename T, int NT, int DEPTH>
-__device__ __forceinline__ void gemm_group(const T* const (&wt)[NT], int K, const ActDesc& A, const Misc* ms, int m,
-                                           char* act) {
-  constexpr int KB = 256 / (int)sizeof(T);
-  constexpr int EPV = TT<T>::EPV;
-  const int lane = LANE, wave = WAVE;
-  const int r = lane & 15, g = lane >> 4;
-  const int nkb = (K + KB - 1) / KB;
-  int kcb = (LS_ACT_BYTES / (m * 256)) & ~(4 * DEPTH - 1);
-  const int nkb_up = (nkb + 4 * DEPTH - 1) & ~(4 * DEPTH - 1);
-  if (kcb > nkb_up) kcb = nkb_up;
-  const int rs_units = kcb * 16;
-
-  const T* rp[NT];
-#pragma unroll
-  for (int t = 0; t < NT; ++t) rp[t] = wt[t] ? wt[t] + (size_t)r * K + g * EPV : nullptr;
-
+struct Gemm {
+  static constexpr int KB = 256 / (int)sizeof(T);
+  static constexpr int EPV = TT<T>::EPV;
   uint4 slot[DEPTH][NT][4];
-  auto load_slot = [&](int s, int kb) {
+  const T* rp[NT];
+  int K, nkb;
+
+  __device__ __forceinline__ void load_slot(int s, int kb) {
+    const int g = LANE >> 4;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
 #pragma unroll
@@ -233,49 +269,65 @@ __device__ __forceinline__ void gemm_group(const T* const (&wt)[NT], int K, cons
           slot[s][t][j] = make_uint4(0, 0, 0, 0);
       }
     }
-  };
-#pragma unroll
-  for (int s = 0; s < DEPTH; ++s) load_slot(s, wave + 4 * s);
+  }
 
-  f32x4 acc[NT];
+  __device__ __forceinline__ void begin(const T* const (&wt)[NT], int K_) {
+    const int r = LANE & 15, g = LANE >> 4;
+    K = K_;
+    nkb = (K + KB - 1) / KB;
 #pragma unroll
-  for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < NT; ++t) rp[t] = wt[t] ? wt[t] + (size_t)r * K + g * EPV : nullptr;
+#pragma unroll
+    for (int s = 0; s < DEPTH; ++s) load_slot(s, WAVE + 4 * s);
+  }
 
-  lds_barrier();  // the previous user of the LDS region is done with it
-  for (int c0 = 0; c0 < nkb; c0 += kcb) {
-    if (c0) lds_barrier();
-    const int cend = (c0 + kcb < nkb) ? c0 + kcb : nkb;
-    stage_act<T>(A, ms, m, K, c0 * KB, (cend - c0) * KB, rs_units, act);
-    lds_barrier();
-    for (int kb0 = c0 + wave; kb0 < cend; kb0 += 4 * DEPTH) {
+  __device__ __forceinline__ void run(const ActDesc& A, const Misc* ms, int m, char* act) {
+    const int lane = LANE, wave = WAVE;
+    const int r = lane & 15, g = lane >> 4;
+    int kcb = (LS_ACT_BYTES / (m * 256)) & ~(4 * DEPTH - 1);
+    const int nkb_up = (nkb + 4 * DEPTH - 1) & ~(4 * DEPTH - 1);
+    if (kcb > nkb_up) kcb = nkb_up;
+    const int rs_units = kcb * 16;
+    f32x4 acc[NT];
 #pragma unroll
-      for (int s = 0; s < DEPTH; ++s) {
-        const int kb = kb0 + 4 * s;
-        if (kb < cend) {
-          uint4 b[4];
+    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    lds_barrier();  // the previous user of the LDS region is done with it
+    for (int c0 = 0; c0 < nkb; c0 += kcb) {
+      if (c0) lds_barrier();
+      const int cend = (c0 + kcb < nkb) ? c0 + kcb : nkb;
+      stage_act<T>(A, ms, m, K, c0 * KB, (cend - c0) * KB, rs_units, act);
+      lds_barrier();
+      for (int kb0 = c0 + wave; kb0 < cend; kb0 += 4 * DEPTH) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int u = (kb - c0) * 16 + j * 4 + g;
-            const int pu = (u & ~15) | ((u ^ r) & 15);
-            b[j] = (r < m) ? *reinterpret_cast<const uint4*>(act + ((size_t)r * rs_units + pu) * 16)
-                           : make_uint4(0, 0, 0, 0);
+        for (int s = 0; s < DEPTH; ++s) {
+          const int kb = kb0 + 4 * s;
+          if (kb < cend) {
+            uint4 b[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const int u = (kb - c0) * 16 + j * 4 + g;
+              const int pu = (u & ~15) | ((u ^ r) & 15);
+              b[j] = (r < m) ? *reinterpret_cast<const uint4*>(act + ((size_t)r * rs_units + pu) * 16)
+                             : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) TT<T>::mma(acc[t], slot[s][t][j], b[j]);
+            }
+            load_slot(s, kb + 4 * DEPTH);
           }
-#pragma unroll
-          for (int t = 0; t < NT; ++t) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) TT<T>::mma(acc[t], slot[s][t][j], b[j]);
-          }
-          load_slot(s, kb + 4 * DEPTH);
         }
       }
     }
-  }
-  lds_barrier();
-  f32x4* red = reinterpret_cast<f32x4*>(act);
+    lds_barrier();
+    f32x4* red = reinterpret_cast<f32x4*>(act);
 #pragma unroll
-  for (int t = 0; t < NT; ++t) red[(wave * NT + t) * 64 + lane] = acc[t];
-  lds_barrier();
-}
+    for (int t = 0; t < NT; ++t) red[(wave * NT + t) * 64 + lane] = acc[t];
+    lds_barrier();
+  }
+};
 
 template <int NT>
 __device__ __forceinline__ f32x4 tile_sum(const char* act, int t) {
@@ -291,7 +343,7 @@ __device__ __forceinline__ f32x4 tile_sum(const char* act, int t) {
 
 // 1/sqrt(mean(x^2) + eps) for the pass rows, into Misc::rinv.
 template <typename T>
-__device__ __noinline__ void compute_rinv(const LsKParams& P, const PassCtx& pc, bool from_embed, Misc* ms) {
+__device__ __forceinline__ void compute_rinv(const LsKParams& P, const PassCtx& pc, bool from_embed, Misc* ms) {
   const int lane = LANE, wave = WAVE;
   for (int n = wave; n < pc.m; n += 4) {
     float s = 0.f;
@@ -301,20 +353,20 @@ __device__ __noinline__ void compute_rinv(const LsKParams& P, const PassCtx& pc,
     } else {
       const int nt = P.dm / 16;
       const float* q = P.ssq + (size_t)(pc.row0 + n) * nt;
-      for (int k = lane; k < nt; k += 64) s += q[k];
+      for (int k = lane; k < nt; k += 64) s += ldcf(q + k);
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
     if (lane == 0) ms->rinv[n] = 1.0f / sqrtf(s / (float)P.dm + P.eps);
   }
-  __syncthreads();
+  lds_barrier();
 }
 
 // ------------------------------------------------------------------------------------------
 // Stage A: RMSNorm + QKV projection + RoPE + KV append.  A work item is a pair of 16-row tiles:
 // for q and k the rows (j, j + hd/2) that one rotation mixes, for v two adjacent tiles.
 template <typename T, int NT>
-__device__ __noinline__ void stage_qkv(const LsKParams& P, const PassCtx& pc, int l, Misc* ms, char* act) {
+__device__ __noinline__ bool stage_qkv(const LsKParams& P, const PassCtx& pc, int l, Misc* ms, char* act) {
   constexpr int DEPTH = (NT == 4) ? 2 : 4;
   constexpr int IPG = NT / 2;
   const LsLayerW& W = P.layers[l];
@@ -330,8 +382,7 @@ __device__ __noinline__ void stage_qkv(const LsKParams& P, const PassCtx& pc, in
   A.ld = dm;
   A.gain = W.attn_norm;
   const int lane = LANE, wave = WAVE, n = lane & 15, g = lane >> 4;
-  for (int grp = blockIdx.x; grp < groups; grp += gridDim.x) {
-    const T* wt[NT];
+  auto tiles_of = [&](int grp, const T* (&wt)[NT]) {
 #pragma unroll
     for (int u = 0; u < IPG; ++u) {
       const int item = grp * IPG + u;
@@ -352,7 +403,16 @@ __device__ __noinline__ void stage_qkv(const LsKParams& P, const PassCtx& pc, in
       wt[2 * u] = t0;
       wt[2 * u + 1] = t1;
     }
-    gemm_group<T, NT, DEPTH>(wt, dm, A, ms, pc.m, act);
+  };
+  Gemm<T, NT, DEPTH> G;
+  const T* wt[NT];
+  int grp = blockIdx.x;
+  if (grp < groups) { tiles_of(grp, wt); G.begin(wt, dm); }
+  if (!grid_barrier(P, ms)) return false;
+  compute_rinv<T>(P, pc, emb, ms);
+  for (; grp < groups; grp += gridDim.x) {
+    if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, dm); }
+    G.run(A, ms, pc.m, act);
     if (wave < IPG) {
       const int item = grp * IPG + wave;
       if (item < items) {
@@ -365,28 +425,31 @@ __device__ __noinline__ void stage_qkv(const LsKParams& P, const PassCtx& pc, in
             const int h = it / pph, jb = it - h * pph;
             T* dst = isq ? static_cast<T*>(P.qbuf) + (size_t)n * P.qd + h * hd
                          : static_cast<T*>(P.kcache) + (((size_t)l * P.nkv + h) * P.max_seq + pos) * hd;
+            float lo[4], hi[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
               const int dj = jb * 16 + 4 * g + j;
               const float c = P.rope_cos[(size_t)pos * half + dj], s = P.rope_sin[(size_t)pos * half + dj];
-              TT<T>::st(dst + dj, a[j] * c - b[j] * s);
-              TT<T>::st(dst + dj + half, b[j] * c + a[j] * s);
+              lo[j] = a[j] * c - b[j] * s;
+              hi[j] = b[j] * c + a[j] * s;
             }
+            TT<T>::stc4(dst + jb * 16 + 4 * g, lo);
+            TT<T>::stc4(dst + jb * 16 + 4 * g + half, hi);
           } else {
             const int it = item - nq_items - nk_items;
             const int row = it * 32;  // within kv_dim
             const int h = row / hd, d0 = row - h * hd;
             T* dst = static_cast<T*>(P.vcache) + (((size_t)l * P.nkv + h) * P.max_seq + pos) * hd + d0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              TT<T>::st(dst + 4 * g + j, a[j]);
-              TT<T>::st(dst + 16 + 4 * g + j, b[j]);
-            }
+            const float va[4] = {a[0], a[1], a[2], a[3]}, vb[4] = {b[0], b[1], b[2], b[3]};
+            TT<T>::stc4(dst + 4 * g, va);
+            TT<T>::stc4(dst + 16 + 4 * g, vb);
           }
         }
       }
     }
   }
+  drain_vmem();
+  return true;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -394,7 +457,7 @@ __device__ __noinline__ void stage_qkv(const LsKParams& P, const PassCtx& pc, in
 // A work item is (kv head, 64-position tile); the last workgroup to finish a kv head merges the
 // per-tile partial softmaxes in tile order.
 template <typename T, int HD>
-__device__ __noinline__ void stage_attn(const LsKParams& P, const PassCtx& pc, int l, Misc* ms, char* act) {
+__device__ __noinline__ bool stage_attn(const LsKParams& P, const PassCtx& pc, int l, Misc* ms, char* act) {
   constexpr int TP = LS_ATTN_TILE;
   constexpr int SEG = HD / 4;           // dims per thread in the q.k product
   constexpr int DQ = HD / 4;            // threads across one V row (4 dims each)
@@ -414,6 +477,7 @@ __device__ __noinline__ void stage_attn(const LsKParams& P, const PassCtx& pc, i
   const T* kc = static_cast<const T*>(P.kcache) + (size_t)l * P.nkv * P.max_seq * HD;
   const T* vc = static_cast<const T*>(P.vcache) + (size_t)l * P.nkv * P.max_seq * HD;
 
+  if (!grid_barrier(P, ms)) return false;
   for (int item = blockIdx.x; item < items; item += gridDim.x) {
     const int c = item / ntiles, ti = item - c * ntiles;
     const int kp0 = ti * TP;
@@ -424,7 +488,7 @@ __device__ __noinline__ void stage_attn(const LsKParams& P, const PassCtx& pc, i
     if (u < nvalid) {
       const T* kp = kc + ((size_t)c * P.max_seq + kp0 + u) * HD + seg * SEG;
 #pragma unroll
-      for (int e = 0; e < SEG; e += TT<T>::EPV) TT<T>::unpack(*reinterpret_cast<const uint4*>(kp + e), &kreg[e]);
+      for (int e = 0; e < SEG; e += 4) TT<T>::ldc4(kp + e, &kreg[e]);
     } else {
 #pragma unroll
       for (int e = 0; e < SEG; ++e) kreg[e] = 0.f;
@@ -435,7 +499,7 @@ __device__ __noinline__ void stage_attn(const LsKParams& P, const PassCtx& pc, i
     for (int kk = 0; kk < KPP; ++kk) {
       const int key = part * KPP + kk;
       if (key < nvalid) {
-        TT<T>::ld4(vc + ((size_t)c * P.max_seq + kp0 + key) * HD + dq * 4, vreg[kk]);
+        TT<T>::ldc4(vc + ((size_t)c * P.max_seq + kp0 + key) * HD + dq * 4, vreg[kk]);
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e) vreg[kk][e] = 0.f;
@@ -445,13 +509,15 @@ __device__ __noinline__ void stage_attn(const LsKParams& P, const PassCtx& pc, i
 
     for (int qb = 0; qb < nQ; qb += 16) {
       const int nqb = (nQ - qb < 16) ? nQ - qb : 16;
-      __syncthreads();
-      for (int idx = tid; idx < nqb * HD; idx += LS_THREADS) {
-        const int qi = idx / HD, dim = idx - qi * HD;
+      lds_barrier();
+      for (int idx = tid; idx < nqb * (HD / 4); idx += LS_THREADS) {
+        const int qi = idx / (HD / 4), d4 = (idx - qi * (HD / 4)) * 4;
         const int qg = qb + qi, n = qg / G, gq = qg - n * G;
-        qs[qi * HD + dim] = TT<T>::ld(static_cast<const T*>(P.qbuf) + (size_t)n * P.qd + (c * G + gq) * HD + dim);
+        float f[4];
+        TT<T>::ldc4(static_cast<const T*>(P.qbuf) + (size_t)n * P.qd + (c * G + gq) * HD + d4, f);
+        *reinterpret_cast<float4*>(qs + qi * HD + d4) = make_float4(f[0], f[1], f[2], f[3]);
       }
-      __syncthreads();
+      lds_barrier();
       for (int qi = 0; qi < nqb; ++qi) {
         const float* q = qs + qi * HD + seg * SEG;
         float dot = 0.f;
@@ -467,7 +533,7 @@ __device__ __noinline__ void stage_attn(const LsKParams& P, const PassCtx& pc, i
           sc[qi * TP + u] = (u < nvalid && kp0 + u <= qpos) ? dot * P.attn_scale : -INFINITY;
         }
       }
-      __syncthreads();
+      lds_barrier();
       for (int qi = wave; qi < nqb; qi += 4) {
         const float s = sc[qi * TP + lane];
         float mx = s;
@@ -480,7 +546,7 @@ __device__ __noinline__ void stage_attn(const LsKParams& P, const PassCtx& pc, i
         sc[qi * TP + lane] = p;
         if (lane == 0) { smx[qi] = mx; ssm[qi] = sum; }
       }
-      __syncthreads();
+      lds_barrier();
       for (int qi = 0; qi < nqb; ++qi) {
         float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
 #pragma unroll
@@ -494,51 +560,59 @@ __device__ __noinline__ void stage_attn(const LsKParams& P, const PassCtx& pc, i
         }
         if (lane < DQ) *reinterpret_cast<float4*>(red + (wave * 16 + qi) * HD + lane * 4) = make_float4(o0, o1, o2, o3);
       }
-      __syncthreads();
-      for (int idx = tid; idx < nqb * HD; idx += LS_THREADS) {
-        const int qi = idx / HD, dim = idx - qi * HD;
-        const float o = ((red[(0 * 16 + qi) * HD + dim] + red[(1 * 16 + qi) * HD + dim]) + red[(2 * 16 + qi) * HD + dim]) +
-                        red[(3 * 16 + qi) * HD + dim];
+      lds_barrier();
+      for (int idx = tid; idx < nqb * (HD / 2); idx += LS_THREADS) {
+        const int qi = idx / (HD / 2), dim = (idx - qi * (HD / 2)) * 2;
+        float o[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+          o[e] = ((red[(0 * 16 + qi) * HD + dim + e] + red[(1 * 16 + qi) * HD + dim + e]) +
+                  red[(2 * 16 + qi) * HD + dim + e]) + red[(3 * 16 + qi) * HD + dim + e];
         float* dst = pout + (size_t)(qb + qi) * PSTRIDE;
-        dst[dim] = o;
-        if (dim == 0) { dst[HD] = smx[qi]; dst[HD + 1] = ssm[qi]; }
+        stcf2(dst + dim, o[0], o[1]);
+        if (dim == 0) stcf2(dst + HD, smx[qi], ssm[qi]);
       }
     }
-    // last arriver of this kv head merges the tiles
-    __threadfence();
-    __syncthreads();
+    // last arriver of this kv head merges the tiles (partials are coherent stores: once they have
+    // completed, whoever sees the counter reach ntiles sees them)
+    drain_vmem();
+    lds_barrier();
     if (tid == 0) {
-      const unsigned old = __hip_atomic_fetch_add(P.attn_cnt + c, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned old = __hip_atomic_fetch_add(P.attn_cnt + c, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       ms->flag = (old == (unsigned)(ntiles - 1));
     }
-    __syncthreads();
+    lds_barrier();
     if (ms->flag) {
-      __threadfence();
       const float* pin = P.attn_part + ((size_t)(c * P.max_tiles) * 64) * PSTRIDE;
-      for (int idx = tid; idx < nQ * HD; idx += LS_THREADS) {
-        const int qg = idx / HD, dim = idx - qg * HD;
+      for (int idx = tid; idx < nQ * (HD / 2); idx += LS_THREADS) {
+        const int qg = idx / (HD / 2), dim = (idx - qg * (HD / 2)) * 2;
         float M = -INFINITY;
-        for (int t = 0; t < ntiles; ++t) M = fmaxf(M, pin[((size_t)t * 64 + qg) * PSTRIDE + HD]);
-        float num = 0.f, den = 0.f;
+        for (int t = 0; t < ntiles; ++t) M = fmaxf(M, ldcf(pin + ((size_t)t * 64 + qg) * PSTRIDE + HD));
+        float n0 = 0.f, n1 = 0.f, den = 0.f;
         for (int t = 0; t < ntiles; ++t) {
           const float* pp = pin + ((size_t)t * 64 + qg) * PSTRIDE;
-          const float w = (pp[HD] == -INFINITY) ? 0.f : expf(pp[HD] - M);
-          num += w * pp[dim];
-          den += w * pp[HD + 1];
+          const float2 stt = ldcf2(pp + HD);
+          const float2 ov = ldcf2(pp + dim);
+          const float w = (stt.x == -INFINITY) ? 0.f : expf(stt.x - M);
+          n0 += w * ov.x;
+          n1 += w * ov.y;
+          den += w * stt.y;
         }
         const int n = qg / G, gq = qg - n * G;
-        TT<T>::st(static_cast<T*>(P.obuf) + (size_t)n * P.qd + (c * G + gq) * HD + dim, num / den);
+        TT<T>::stc2(static_cast<T*>(P.obuf) + (size_t)n * P.qd + (c * G + gq) * HD + dim, n0 / den, n1 / den);
       }
       if (tid == 0) __hip_atomic_store(P.attn_cnt + c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
+  drain_vmem();
+  return true;
 }
 
 // ------------------------------------------------------------------------------------------
 // Stages C and E: x += W * in  (O projection of the attention output; down projection of the
 // SwiGLU output), plus the per-tile sums of squares the next RMSNorm needs.
 template <typename T, int NT>
-__device__ __noinline__ void stage_resid(const LsKParams& P, const PassCtx& pc, int l, bool is_down, Misc* ms, char* act) {
+__device__ __noinline__ bool stage_resid(const LsKParams& P, const PassCtx& pc, int l, bool is_down, Misc* ms, char* act) {
   constexpr int DEPTH = (NT == 4) ? 2 : 4;
   const LsLayerW& W = P.layers[l];
   const int dm = P.dm;
@@ -553,14 +627,21 @@ __device__ __noinline__ void stage_resid(const LsKParams& P, const PassCtx& pc, 
   A.gain = nullptr;
   const bool emb = !is_down && pc.embed_src && l == pc.l0;  // residual comes from the embedding row
   const int lane = LANE, wave = WAVE, n = lane & 15, g = lane >> 4;
-  for (int grp = blockIdx.x; grp < groups; grp += gridDim.x) {
-    const T* wt[NT];
+  auto tiles_of = [&](int grp, const T* (&wt)[NT]) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       const int tile = grp * NT + t;
       wt[t] = tile < tiles ? wmat + (size_t)tile * 16 * K : nullptr;
     }
-    gemm_group<T, NT, DEPTH>(wt, K, A, ms, pc.m, act);
+  };
+  Gemm<T, NT, DEPTH> G;
+  const T* wt[NT];
+  int grp = blockIdx.x;
+  if (grp < groups) { tiles_of(grp, wt); G.begin(wt, K); }
+  if (!grid_barrier(P, ms)) return false;
+  for (; grp < groups; grp += gridDim.x) {
+    if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, K); }
+    G.run(A, ms, pc.m, act);
     for (int t = wave; t < NT; t += 4) {
       const int tile = grp * NT + t;
       if (tile >= tiles) continue;
@@ -574,10 +655,11 @@ __device__ __noinline__ void stage_resid(const LsKParams& P, const PassCtx& pc, 
 #pragma unroll
           for (int j = 0; j < 4; ++j) nx[j] = TT<T>::ld(e + j) + v[j];
         } else {
-          const float4 o = *reinterpret_cast<const float4*>(xr);
-          nx[0] = o.x + v[0]; nx[1] = o.y + v[1]; nx[2] = o.z + v[2]; nx[3] = o.w + v[3];
+          const float2 o0 = ldcf2(xr), o1 = ldcf2(xr + 2);
+          nx[0] = o0.x + v[0]; nx[1] = o0.y + v[1]; nx[2] = o1.x + v[2]; nx[3] = o1.y + v[3];
         }
-        *reinterpret_cast<float4*>(xr) = make_float4(nx[0], nx[1], nx[2], nx[3]);
+        stcf2(xr, nx[0], nx[1]);
+        stcf2(xr + 2, nx[2], nx[3]);
         if (is_down && P.capture != nullptr)
           *reinterpret_cast<float4*>(P.capture + ((size_t)l * P.max_seq + pc.pos0 + n) * dm + row) =
               make_float4(nx[0], nx[1], nx[2], nx[3]);
@@ -585,16 +667,18 @@ __device__ __noinline__ void stage_resid(const LsKParams& P, const PassCtx& pc, 
       float s = nx[0] * nx[0] + nx[1] * nx[1] + nx[2] * nx[2] + nx[3] * nx[3];
       s += __shfl_xor(s, 16);
       s += __shfl_xor(s, 32);
-      if (g == 0 && n < pc.m) P.ssq[(size_t)(pc.row0 + n) * tiles + tile] = s;
+      if (g == 0 && n < pc.m) stcf(P.ssq + (size_t)(pc.row0 + n) * tiles + tile, s);
     }
   }
+  drain_vmem();
+  return true;
 }
 
 // ------------------------------------------------------------------------------------------
 // Stage D: RMSNorm + gate/up projection + SwiGLU.  A work item pairs the gate tile and the up
 // tile of the same 16 features.
 template <typename T, int NT>
-__device__ __noinline__ void stage_gu(const LsKParams& P, const PassCtx& pc, int l, Misc* ms, char* act) {
+__device__ __noinline__ bool stage_gu(const LsKParams& P, const PassCtx& pc, int l, Misc* ms, char* act) {
   constexpr int DEPTH = (NT == 4) ? 2 : 4;
   constexpr int IPG = NT / 2;
   const LsLayerW& W = P.layers[l];
@@ -607,35 +691,46 @@ __device__ __noinline__ void stage_gu(const LsKParams& P, const PassCtx& pc, int
   A.ld = dm;
   A.gain = W.ffn_norm;
   const int lane = LANE, wave = WAVE, n = lane & 15, g = lane >> 4;
-  for (int grp = blockIdx.x; grp < groups; grp += gridDim.x) {
-    const T* wt[NT];
+  auto tiles_of = [&](int grp, const T* (&wt)[NT]) {
 #pragma unroll
     for (int u = 0; u < IPG; ++u) {
       const int item = grp * IPG + u;
       wt[2 * u] = item < items ? static_cast<const T*>(W.wg) + (size_t)item * 16 * dm : nullptr;
       wt[2 * u + 1] = item < items ? static_cast<const T*>(W.wu) + (size_t)item * 16 * dm : nullptr;
     }
-    gemm_group<T, NT, DEPTH>(wt, dm, A, ms, pc.m, act);
+  };
+  Gemm<T, NT, DEPTH> G;
+  const T* wt[NT];
+  int grp = blockIdx.x;
+  if (grp < groups) { tiles_of(grp, wt); G.begin(wt, dm); }
+  if (!grid_barrier(P, ms)) return false;
+  compute_rinv<T>(P, pc, false, ms);
+  for (; grp < groups; grp += gridDim.x) {
+    if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, dm); }
+    G.run(A, ms, pc.m, act);
     if (wave < IPG) {
       const int item = grp * IPG + wave;
       if (item < items && n < pc.m) {
         const f32x4 gt = tile_sum<NT>(act, 2 * wave), up = tile_sum<NT>(act, 2 * wave + 1);
-        T* dst = static_cast<T*>(P.actbuf) + (size_t)n * P.ffn + item * 16 + 4 * g;
+        float o[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const float z = gt[j];
-          TT<T>::st(dst + j, (z / (1.0f + expf(-z))) * up[j]);
+          o[j] = (z / (1.0f + expf(-z))) * up[j];
         }
+        TT<T>::stc4(static_cast<T*>(P.actbuf) + (size_t)n * P.ffn + item * 16 + 4 * g, o);
       }
     }
   }
+  drain_vmem();
+  return true;
 }
 
 // ------------------------------------------------------------------------------------------
 // Head: final RMSNorm + LM head + per-row argmax (highest value, lowest index on ties) with the
 // runner-up value kept for the margin.  Each workgroup writes one candidate per row.
 template <typename T>
-__device__ __noinline__ void stage_head(const LsKParams& P, const PassCtx& pc, Misc* ms, char* act) {
+__device__ __noinline__ bool stage_head(const LsKParams& P, const PassCtx& pc, Misc* ms, char* act) {
   constexpr int NT = 4, DEPTH = 2;
   const int dm = P.dm;
   const int tiles = P.vocab / 16;
@@ -646,16 +741,24 @@ __device__ __noinline__ void stage_head(const LsKParams& P, const PassCtx& pc, M
   A.ld = dm;
   A.gain = P.final_norm;
   const int lane = LANE, wave = WAVE, n = lane & 15, g = lane >> 4;
-  Best best;
-  best.v1 = -INFINITY; best.i1 = INT_MAX; best.v2 = -INFINITY;
-  for (int grp = blockIdx.x; grp < groups; grp += gridDim.x) {
-    const T* wt[NT];
+  auto tiles_of = [&](int grp, const T* (&wt)[NT]) {
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       const int tile = grp * NT + t;
       wt[t] = tile < tiles ? static_cast<const T*>(P.lm_head) + (size_t)tile * 16 * dm : nullptr;
     }
-    gemm_group<T, NT, DEPTH>(wt, dm, A, ms, pc.m, act);
+  };
+  Best best;
+  best.v1 = -INFINITY; best.i1 = INT_MAX; best.v2 = -INFINITY;
+  Gemm<T, NT, DEPTH> G;
+  const T* wt[NT];
+  int grp = blockIdx.x;
+  if (grp < groups) { tiles_of(grp, wt); G.begin(wt, dm); }
+  if (!grid_barrier(P, ms)) return false;
+  compute_rinv<T>(P, pc, false, ms);
+  for (; grp < groups; grp += gridDim.x) {
+    if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, dm); }
+    G.run(A, ms, pc.m, act);
     const int tile = grp * NT + wave;
     if (tile < tiles) {
       const f32x4 v = tile_sum<NT>(act, wave);
@@ -669,35 +772,41 @@ __device__ __noinline__ void stage_head(const LsKParams& P, const PassCtx& pc, M
   }
   best = best_merge(best, best_shfl_xor(best, 16));
   best = best_merge(best, best_shfl_xor(best, 32));
+  lds_barrier();
   if (g == 0) ms->wb[wave][n] = best;
-  __syncthreads();
+  lds_barrier();
   if (TID < LS_ROWS) {
     Best b = ms->wb[0][TID];
     b = best_merge(b, ms->wb[1][TID]);
     b = best_merge(b, ms->wb[2][TID]);
     b = best_merge(b, ms->wb[3][TID]);
-    *reinterpret_cast<float4*>(P.cand + ((size_t)blockIdx.x * LS_ROWS + TID) * 4) =
-        make_float4(b.v1, __int_as_float(b.i1), b.v2, 0.f);
+    float* dst = P.cand + ((size_t)blockIdx.x * LS_ROWS + TID) * 4;
+    stcf2(dst, b.v1, __int_as_float(b.i1));
+    stcf2(dst + 2, b.v2, 0.f);
   }
+  drain_vmem();
+  return true;
 }
 
-// After the barrier that follows the head stage: every workgroup merges all candidates.
-__device__ __noinline__ void reduce_cands(const LsKParams& P, const PassCtx& pc, Misc* ms) {
+// After the head stage: every workgroup merges all candidates (same result everywhere).
+__device__ __noinline__ bool reduce_cands(const LsKParams& P, const PassCtx& pc, Misc* ms) {
+  if (!grid_barrier(P, ms)) return false;
   const int lane = LANE, wave = WAVE;
   for (int n = 0; n < pc.m; ++n) {
     Best b;
     b.v1 = -INFINITY; b.i1 = INT_MAX; b.v2 = -INFINITY;
     for (int w = TID; w < (int)gridDim.x; w += LS_THREADS) {
-      const float4 c = *reinterpret_cast<const float4*>(P.cand + ((size_t)w * LS_ROWS + n) * 4);
+      const float* src = P.cand + ((size_t)w * LS_ROWS + n) * 4;
+      const float2 c0 = ldcf2(src), c1 = ldcf2(src + 2);
       Best cb;
-      cb.v1 = c.x; cb.i1 = __float_as_int(c.y); cb.v2 = c.z;
+      cb.v1 = c0.x; cb.i1 = __float_as_int(c0.y); cb.v2 = c1.x;
       b = best_merge(b, cb);
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) b = best_merge(b, best_shfl_xor(b, o));
     if (lane == 0) ms->wb[wave][n] = b;
   }
-  __syncthreads();
+  lds_barrier();
   if (TID < pc.m) {
     Best b = ms->wb[0][TID];
     b = best_merge(b, ms->wb[1][TID]);
@@ -706,35 +815,34 @@ __device__ __noinline__ void reduce_cands(const LsKParams& P, const PassCtx& pc,
     ms->r_tok[TID] = b.i1;
     ms->r_margin[TID] = b.v1 - b.v2;
   }
-  __syncthreads();
+  lds_barrier();
+  return true;
 }
 
 // ------------------------------------------------------------------------------------------
+// One pass.  Every stage starts with the grid barrier that orders it after the stage before
+// (weight loads for its first tiles are issued ahead of that barrier).
 template <typename T>
 __device__ bool run_pass(const LsKParams& P, const PassCtx& pc, Misc* ms, char* act) {
   for (int l = pc.l0; l < pc.l1; ++l) {
-    compute_rinv<T>(P, pc, pc.embed_src && l == pc.l0, ms);
-    if (P.nt_qkv == 4) stage_qkv<T, 4>(P, pc, l, ms, act); else stage_qkv<T, 2>(P, pc, l, ms, act);
-    if (!grid_barrier(P, ms)) return false;
-    if (P.hd == 128) stage_attn<T, 128>(P, pc, l, ms, act); else stage_attn<T, 64>(P, pc, l, ms, act);
-    if (!grid_barrier(P, ms)) return false;
-    if (P.nt_o == 4) stage_resid<T, 4>(P, pc, l, false, ms, act);
-    else if (P.nt_o == 2) stage_resid<T, 2>(P, pc, l, false, ms, act);
-    else stage_resid<T, 1>(P, pc, l, false, ms, act);
-    if (!grid_barrier(P, ms)) return false;
-    compute_rinv<T>(P, pc, false, ms);
-    if (P.nt_gu == 4) stage_gu<T, 4>(P, pc, l, ms, act); else stage_gu<T, 2>(P, pc, l, ms, act);
-    if (!grid_barrier(P, ms)) return false;
-    if (P.nt_down == 4) stage_resid<T, 4>(P, pc, l, true, ms, act);
-    else if (P.nt_down == 2) stage_resid<T, 2>(P, pc, l, true, ms, act);
-    else stage_resid<T, 1>(P, pc, l, true, ms, act);
-    if (!grid_barrier(P, ms)) return false;
+    bool ok = (P.nt_qkv == 4) ? stage_qkv<T, 4>(P, pc, l, ms, act) : stage_qkv<T, 2>(P, pc, l, ms, act);
+    if (!ok) return false;
+    ok = (P.hd == 128) ? stage_attn<T, 128>(P, pc, l, ms, act) : stage_attn<T, 64>(P, pc, l, ms, act);
+    if (!ok) return false;
+    ok = (P.nt_o == 4) ? stage_resid<T, 4>(P, pc, l, false, ms, act)
+       : (P.nt_o == 2) ? stage_resid<T, 2>(P, pc, l, false, ms, act)
+                       : stage_resid<T, 1>(P, pc, l, false, ms, act);
+    if (!ok) return false;
+    ok = (P.nt_gu == 4) ? stage_gu<T, 4>(P, pc, l, ms, act) : stage_gu<T, 2>(P, pc, l, ms, act);
+    if (!ok) return false;
+    ok = (P.nt_down == 4) ? stage_resid<T, 4>(P, pc, l, true, ms, act)
+       : (P.nt_down == 2) ? stage_resid<T, 2>(P, pc, l, true, ms, act)
+                          : stage_resid<T, 1>(P, pc, l, true, ms, act);
+    if (!ok) return false;
   }
   if (pc.head) {
-    compute_rinv<T>(P, pc, false, ms);
-    stage_head<T>(P, pc, ms, act);
-    if (!grid_barrier(P, ms)) return false;
-    reduce_cands(P, pc, ms);
+    if (!stage_head<T>(P, pc, ms, act)) return false;
+    if (!reduce_cands(P, pc, ms)) return false;
   }
   return true;
 }
@@ -899,8 +1007,13 @@ static const void* kernel_for(int kind, int dtype_is_bf16) {
 
 extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid, hipStream_t stream) {
   void* args[1] = {const_cast<LsKParams*>(p)};
-  hipError_t e = hipLaunchCooperativeKernel(kernel_for(p->kind, dtype_is_bf16), dim3(grid), dim3(LS_THREADS), args,
-                                            LS_SMEM_BYTES, stream);
+  // The grid is sized to be co-resident (occupancy x compute units) and the barrier wait is bounded,
+  // so an ordinary launch is used; LS_COOPERATIVE_LAUNCH=1 asks the runtime to guarantee residency.
+  static const bool coop = []() { const char* v = getenv("LS_COOPERATIVE_LAUNCH"); return v != nullptr && v[0] == '1'; }();
+  hipError_t e = coop ? hipLaunchCooperativeKernel(kernel_for(p->kind, dtype_is_bf16), dim3(grid), dim3(LS_THREADS),
+                                                   args, LS_SMEM_BYTES, stream)
+                      : hipLaunchKernel(kernel_for(p->kind, dtype_is_bf16), dim3(grid), dim3(LS_THREADS), args,
+                                        LS_SMEM_BYTES, stream);
   return e == hipSuccess ? 0 : (int)e;
 }
 
