@@ -150,6 +150,11 @@ int ls_peek_round(ls_ctx *ctx, int32_t *host_draft, int32_t *host_verify, float 
  * dev_hidden[l][position][:] (DEVICE float [n_layers][max_seq][d_model]); NULL switches it off. */
 int ls_debug_capture(ls_ctx *ctx, float *dev_hidden);
 
+/* Inspection: from now on every launch appends the timeline of one workgroup to dev_events (DEVICE
+ * uint64[capacity], each entry (100 MHz device clock << 8) | stage tag, restarting at entry 0 per
+ * launch); NULL switches it off.  Used to see where a pass spends its time. */
+int ls_debug_timeline(ls_ctx *ctx, unsigned long long *dev_events, int32_t capacity, int32_t workgroup);
+
 /* Launch shape: workgroups per compute unit (1 or 2) used by later calls; 0 restores the default.
  * Returns the number of workgroups a launch will use, or a negative error. */
 int ls_set_launch(ls_ctx *ctx, int32_t workgroups_per_cu);

@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 EXPORTS = (
     "ls_workspace_bytes", "ls_load_weights", "ls_prefill", "ls_draft", "ls_verify", "ls_generate",
     "ls_generate_early_exit", "ls_score", "ls_get_state", "ls_peek_round", "ls_debug_capture",
-    "ls_set_launch", "ls_strerror", "ls_destroy",
+    "ls_debug_timeline", "ls_set_launch", "ls_strerror", "ls_destroy",
 )
 
 
@@ -102,6 +102,8 @@ def lib() -> C.CDLL:
     L.ls_peek_round.argtypes = [vp, i32p, i32p, f32p, f32p, i32p, vp]
     L.ls_debug_capture.restype = C.c_int
     L.ls_debug_capture.argtypes = [vp, vp]
+    L.ls_debug_timeline.restype = C.c_int
+    L.ls_debug_timeline.argtypes = [vp, vp, i32, i32]
     L.ls_set_launch.restype = C.c_int
     L.ls_set_launch.argtypes = [vp, i32]
     L.ls_strerror.restype = C.c_char_p
@@ -253,6 +255,17 @@ class LsModel:
         n = C.c_int32()
         _check(self.lib.ls_peek_round(self.ctx, D, V, dm, vm, C.byref(n), self._stream()), "ls_peek_round")
         return list(D[:d]), list(V[:d + 1]), list(dm[:d]), list(vm[:d + 1]), n.value
+
+    def debug_timeline(self, capacity: int = 0, workgroup: int = 0):
+        """capacity > 0: returns the device tensor (uint64 as int64) later launches append events to."""
+        if capacity > 0:
+            self._timeline = self.torch.zeros(capacity, dtype=self.torch.int64, device=self.device)
+            _check(self.lib.ls_debug_timeline(self.ctx, C.c_void_p(self._timeline.data_ptr()), capacity, workgroup),
+                   "ls_debug_timeline")
+        else:
+            _check(self.lib.ls_debug_timeline(self.ctx, None, 0, 0), "ls_debug_timeline")
+            self._timeline = None
+        return self._timeline
 
     def debug_capture(self, on: bool = True):
         """Returns the device tensor [n_layers, max_seq, d_model] that later passes fill."""

@@ -81,6 +81,8 @@ struct ls_ctx {
   int pos_bound;    // upper bound of the device-side position, for capacity checks
   hipEvent_t ev[3];
   float* capture;
+  unsigned long long* prof;
+  int prof_cap, prof_wg;
 };
 
 namespace {
@@ -121,6 +123,7 @@ LsKParams program(const ls_ctx* c, int kind) {
   p.E = 0; p.d = 0; p.max_new = 0x7fffffff; p.eos = -1; p.n_tokens = 0; p.layers_used = c->cfg.n_layers;
   p.tokens = nullptr; p.out_tokens = nullptr; p.out_margin = nullptr;
   p.capture = c->capture;
+  p.prof = c->prof; p.prof_cap = c->prof_cap; p.prof_wg = c->prof_wg;
   return p;
 }
 
@@ -163,6 +166,7 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   c->lay = lay;
   c->ws = static_cast<char*>(dev_workspace);
   c->capture = nullptr;
+  c->prof = nullptr; c->prof_cap = 0; c->prof_wg = 0;
   c->prefilled = c->drafted = false;
   c->pos_bound = 0;
 
@@ -375,6 +379,13 @@ int ls_peek_round(ls_ctx* c, int32_t* hd, int32_t* hv, float* hdm, float* hvm, i
 int ls_debug_capture(ls_ctx* c, float* dev_hidden) {
   if (!c) return LS_E_ARG;
   c->capture = dev_hidden;
+  return LS_OK;
+}
+
+int ls_debug_timeline(ls_ctx* c, unsigned long long* dev_events, int32_t capacity, int32_t workgroup) {
+  if (!c) return LS_E_ARG;
+  if (dev_events != nullptr && (capacity < 1 || workgroup < 0 || workgroup >= c->grid)) return LS_E_RANGE;
+  c->prof = dev_events; c->prof_cap = dev_events ? capacity : 0; c->prof_wg = workgroup;
   return LS_OK;
 }
 

@@ -70,6 +70,9 @@ struct LsKParams {
   int32_t *out_tokens;
   float *out_margin;
   int32_t spin_limit;
+  // optional timeline of one workgroup: (100 MHz wall clock << 8) | tag, appended per event
+  unsigned long long *prof;
+  int32_t prof_cap, prof_wg;
 };
 
 #endif

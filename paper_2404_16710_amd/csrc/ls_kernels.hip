@@ -137,8 +137,16 @@ struct Misc {
   unsigned epoch;
   int flag;
   int abort;
+  int prof_n;
 };
 static_assert(sizeof(Misc) <= LS_MISC_BYTES, "Misc must fit its LDS slot");
+
+// Timeline event of the profiled workgroup (debug aid; a null buffer costs one uniform branch).
+#define LS_PROF(tag)                                                                           \
+  do {                                                                                         \
+    if (P.prof != nullptr && (int)blockIdx.x == P.prof_wg && TID == 0 && ms->prof_n < P.prof_cap) \
+      P.prof[ms->prof_n++] = (wall_clock64() << 8) | (unsigned long long)(tag);                 \
+  } while (0)
 
 struct PassCtx {
   int m, row0, pos0, l0, l1;
@@ -407,12 +415,17 @@ __device__ __noinline__ bool stage_qkv(const LsKParams& P, const PassCtx& pc, in
   Gemm<T, NT, DEPTH> G;
   const T* wt[NT];
   int grp = blockIdx.x;
+  LS_PROF(0x10);
   if (grp < groups) { tiles_of(grp, wt); G.begin(wt, dm); }
+  LS_PROF(0x11);
   if (!grid_barrier(P, ms)) return false;
+  LS_PROF(0x12);
   compute_rinv<T>(P, pc, emb, ms);
+  LS_PROF(0x13);
   for (; grp < groups; grp += gridDim.x) {
     if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, dm); }
     G.run(A, ms, pc.m, act);
+    LS_PROF(0x14);
     if (wave < IPG) {
       const int item = grp * IPG + wave;
       if (item < items) {
@@ -448,7 +461,9 @@ __device__ __noinline__ bool stage_qkv(const LsKParams& P, const PassCtx& pc, in
       }
     }
   }
+  LS_PROF(0x15);
   drain_vmem();
+  LS_PROF(0x16);
   return true;
 }
 
@@ -477,7 +492,9 @@ __device__ __noinline__ bool stage_attn(const LsKParams& P, const PassCtx& pc, i
   const T* kc = static_cast<const T*>(P.kcache) + (size_t)l * P.nkv * P.max_seq * HD;
   const T* vc = static_cast<const T*>(P.vcache) + (size_t)l * P.nkv * P.max_seq * HD;
 
+  LS_PROF(0x20);
   if (!grid_barrier(P, ms)) return false;
+  LS_PROF(0x22);
   for (int item = blockIdx.x; item < items; item += gridDim.x) {
     const int c = item / ntiles, ti = item - c * ntiles;
     const int kp0 = ti * TP;
@@ -604,7 +621,9 @@ __device__ __noinline__ bool stage_attn(const LsKParams& P, const PassCtx& pc, i
       if (tid == 0) __hip_atomic_store(P.attn_cnt + c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
+  LS_PROF(0x25);
   drain_vmem();
+  LS_PROF(0x26);
   return true;
 }
 
@@ -637,11 +656,15 @@ __device__ __noinline__ bool stage_resid(const LsKParams& P, const PassCtx& pc, 
   Gemm<T, NT, DEPTH> G;
   const T* wt[NT];
   int grp = blockIdx.x;
+  LS_PROF(is_down ? 0x50 : 0x30);
   if (grp < groups) { tiles_of(grp, wt); G.begin(wt, K); }
+  LS_PROF(is_down ? 0x51 : 0x31);
   if (!grid_barrier(P, ms)) return false;
+  LS_PROF(is_down ? 0x52 : 0x32);
   for (; grp < groups; grp += gridDim.x) {
     if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, K); }
     G.run(A, ms, pc.m, act);
+    LS_PROF(is_down ? 0x54 : 0x34);
     for (int t = wave; t < NT; t += 4) {
       const int tile = grp * NT + t;
       if (tile >= tiles) continue;
@@ -670,7 +693,9 @@ __device__ __noinline__ bool stage_resid(const LsKParams& P, const PassCtx& pc, 
       if (g == 0 && n < pc.m) stcf(P.ssq + (size_t)(pc.row0 + n) * tiles + tile, s);
     }
   }
+  LS_PROF(is_down ? 0x55 : 0x35);
   drain_vmem();
+  LS_PROF(is_down ? 0x56 : 0x36);
   return true;
 }
 
@@ -702,12 +727,17 @@ __device__ __noinline__ bool stage_gu(const LsKParams& P, const PassCtx& pc, int
   Gemm<T, NT, DEPTH> G;
   const T* wt[NT];
   int grp = blockIdx.x;
+  LS_PROF(0x40);
   if (grp < groups) { tiles_of(grp, wt); G.begin(wt, dm); }
+  LS_PROF(0x41);
   if (!grid_barrier(P, ms)) return false;
+  LS_PROF(0x42);
   compute_rinv<T>(P, pc, false, ms);
+  LS_PROF(0x43);
   for (; grp < groups; grp += gridDim.x) {
     if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, dm); }
     G.run(A, ms, pc.m, act);
+    LS_PROF(0x44);
     if (wave < IPG) {
       const int item = grp * IPG + wave;
       if (item < items && n < pc.m) {
@@ -722,7 +752,9 @@ __device__ __noinline__ bool stage_gu(const LsKParams& P, const PassCtx& pc, int
       }
     }
   }
+  LS_PROF(0x45);
   drain_vmem();
+  LS_PROF(0x46);
   return true;
 }
 
@@ -753,12 +785,17 @@ __device__ __noinline__ bool stage_head(const LsKParams& P, const PassCtx& pc, M
   Gemm<T, NT, DEPTH> G;
   const T* wt[NT];
   int grp = blockIdx.x;
+  LS_PROF(0x60);
   if (grp < groups) { tiles_of(grp, wt); G.begin(wt, dm); }
+  LS_PROF(0x61);
   if (!grid_barrier(P, ms)) return false;
+  LS_PROF(0x62);
   compute_rinv<T>(P, pc, false, ms);
+  LS_PROF(0x63);
   for (; grp < groups; grp += gridDim.x) {
     if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, dm); }
     G.run(A, ms, pc.m, act);
+    LS_PROF(0x64);
     const int tile = grp * NT + wave;
     if (tile < tiles) {
       const f32x4 v = tile_sum<NT>(act, wave);
@@ -790,7 +827,9 @@ __device__ __noinline__ bool stage_head(const LsKParams& P, const PassCtx& pc, M
 
 // After the head stage: every workgroup merges all candidates (same result everywhere).
 __device__ __noinline__ bool reduce_cands(const LsKParams& P, const PassCtx& pc, Misc* ms) {
+  LS_PROF(0x70);
   if (!grid_barrier(P, ms)) return false;
+  LS_PROF(0x72);
   const int lane = LANE, wave = WAVE;
   for (int n = 0; n < pc.m; ++n) {
     Best b;
@@ -816,6 +855,7 @@ __device__ __noinline__ bool reduce_cands(const LsKParams& P, const PassCtx& pc,
     ms->r_margin[TID] = b.v1 - b.v2;
   }
   lds_barrier();
+  LS_PROF(0x76);
   return true;
 }
 
@@ -911,6 +951,7 @@ __device__ __forceinline__ void program_body(const LsKParams& P) {
     ms->epoch = 0;
     ms->abort = 0;
     ms->flag = 0;
+    ms->prof_n = 0;
   }
   __syncthreads();
   bool ok = true;
