@@ -59,7 +59,7 @@ typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
   float rope_base, rms_eps;
   int32_t dtype;     /* LS_F32 or LS_BF16                                                   */
-  int32_t max_seq;   /* KV capacity in positions                                            */
+  int32_t max_seq;   /* KV capacity in positions, at most 32768                             */
   int32_t max_draft; /* 1..15                                                               */
 } ls_config;
 /* Supported shapes: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads with ratio <= 4;

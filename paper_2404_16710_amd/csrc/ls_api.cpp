@@ -37,7 +37,7 @@ bool config_ok(const ls_config* c) {
   if (c->d_model < 16 || c->d_model % 16 || c->ffn_dim < 16 || c->ffn_dim % 16) return false;
   if (c->vocab < 16 || c->vocab % 16) return false;
   if (c->max_draft < 1 || c->max_draft > LS_MAX_ROWS - 1) return false;
-  if (c->max_seq < 2 || c->max_seq > (1 << 20)) return false;
+  if (c->max_seq < 2 || c->max_seq > 32768) return false;
   if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f)) return false;
   return true;
 }
@@ -88,17 +88,9 @@ struct ls_ctx {
 namespace {
 
 int choose_nt(int units, int grid, bool pairs) {
-  // tiles per workgroup pass: as many as keeps at least `grid` groups, but never fewer than one unit
-  const int opts_single[3] = {4, 2, 1};
-  const int opts_pair[2] = {4, 2};
-  if (pairs) {
-    for (int nt : opts_pair)
-      if ((units + nt / 2 - 1) / (nt / 2) >= grid) return nt;
-    return 2;
-  }
-  for (int nt : opts_single)
-    if ((units + nt - 1) / nt >= grid) return nt;
-  return 1;
+  // tiles a workgroup multiplies at once: 2 if that still leaves at least `grid` groups
+  if (pairs) return 2;
+  return (units + 1) / 2 >= grid ? 2 : 1;
 }
 
 void set_decomposition(ls_ctx* c) {

@@ -47,18 +47,33 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 // All of this wave's global stores and loads have completed.
 __device__ __forceinline__ void drain_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// Device memory is addressed as global (address space 1), never through flat instructions: a flat
+// access also counts as an LDS access, so the LDS-only barrier would wait for weight loads.
+#define LS_GLOBAL __attribute__((address_space(1)))
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 ldg128(const void* p) {
+  const u32x4_t v = *(const LS_GLOBAL u32x4_t*)(p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ float ldgf(const float* p) { return *(const LS_GLOBAL float*)(p); }
+__device__ __forceinline__ uint32_t ldg16(const void* p) { return *(const LS_GLOBAL uint16_t*)(p); }
+__device__ __forceinline__ void stg128(void* p, const float4& v) {
+  *(LS_GLOBAL f32x4*)(p) = f32x4{v.x, v.y, v.z, v.w};
+}
+
 // Coherent (agent-scope) accesses for data exchanged between workgroups.
 __device__ __forceinline__ uint64_t ldc64(const void* p) {
-  return __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return __hip_atomic_load((const LS_GLOBAL uint64_t*)(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ uint32_t ldc32(const void* p) {
-  return __hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return __hip_atomic_load((const LS_GLOBAL uint32_t*)(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void stc64(void* p, uint64_t v) {
-  __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store((LS_GLOBAL uint64_t*)(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void stc32(void* p, uint32_t v) {
-  __hip_atomic_store(reinterpret_cast<uint32_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store((LS_GLOBAL uint32_t*)(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ float ldcf(const float* p) { return __uint_as_float(ldc32(p)); }
 __device__ __forceinline__ void stcf(float* p, float v) { stc32(p, __float_as_uint(v)); }
@@ -83,7 +98,7 @@ template <> struct TT<float> {
   static __device__ __forceinline__ uint4 pack(const float* f) {
     return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
   }
-  static __device__ __forceinline__ float ld(const float* p) { return *p; }
+  static __device__ __forceinline__ float ld(const float* p) { return ldgf(p); }
   // 4 consecutive elements, coherent
   static __device__ __forceinline__ void ldc4(const float* p, float* f) {
     const float2 a = ldcf2(p), b = ldcf2(p + 2);
@@ -108,7 +123,7 @@ template <> struct TT<bf16_t> {
     return make_uint4(f2bf(f[0]) | (f2bf(f[1]) << 16), f2bf(f[2]) | (f2bf(f[3]) << 16),
                       f2bf(f[4]) | (f2bf(f[5]) << 16), f2bf(f[6]) | (f2bf(f[7]) << 16));
   }
-  static __device__ __forceinline__ float ld(const bf16_t* p) { return bf2f(*p); }
+  static __device__ __forceinline__ float ld(const bf16_t* p) { return bf2f(ldg16(p)); }
   static __device__ __forceinline__ void ldc4(const bf16_t* p, float* f) {
     const uint64_t t = ldc64(p);
     const uint32_t lo = (uint32_t)t, hi = (uint32_t)(t >> 32);
@@ -126,8 +141,11 @@ template <> struct TT<bf16_t> {
 // ------------------------------------------------------------------------------------------
 // LDS bookkeeping
 struct Best { float v1; int i1; float v2; };
+#define LS_LDS_LAYERS 64   // layer pointer tables of the first 64 layers are mirrored in LDS
 
 struct Misc {
+  LsKParams P;                 // kernel parameters (LDS copy: uniform reads without scratch or global trips)
+  LsLayerW lw[LS_LDS_LAYERS];
   LsState st;
   int tok[LS_ROWS];
   float rinv[LS_ROWS];
@@ -141,11 +159,35 @@ struct Misc {
 };
 static_assert(sizeof(Misc) <= LS_MISC_BYTES, "Misc must fit its LDS slot");
 
-// Timeline event of the profiled workgroup (debug aid; a null buffer costs one uniform branch).
-#define LS_PROF(tag)                                                                           \
-  do {                                                                                         \
-    if (P.prof != nullptr && (int)blockIdx.x == P.prof_wg && TID == 0 && ms->prof_n < P.prof_cap) \
-      P.prof[ms->prof_n++] = (wall_clock64() << 8) | (unsigned long long)(tag);                 \
+extern __shared__ __align__(16) char ls_smem[];
+__device__ __forceinline__ Misc* MS() { return reinterpret_cast<Misc*>(ls_smem + LS_ACT_BYTES); }
+// Every stage function starts with this: LDS views that the compiler can see are LDS.
+#define LS_CTX                      \
+  Misc* const ms = MS();            \
+  char* const act = ls_smem;        \
+  const LsKParams& P = ms->P;       \
+  (void)act
+
+__device__ __forceinline__ LsLayerW layer_w(const LsKParams& P, const Misc* ms, int l) {
+  if (l < LS_LDS_LAYERS) return ms->lw[l];
+  LsLayerW w;
+  const LS_GLOBAL uint64_t* src = (const LS_GLOBAL uint64_t*)(P.layers + l);
+  uint64_t* dst = reinterpret_cast<uint64_t*>(&w);
+#pragma unroll
+  for (int i = 0; i < (int)(sizeof(LsLayerW) / 8); ++i) dst[i] = src[i];
+  return w;
+}
+
+// Timeline event of the profiled workgroup (debug aid).  Events go to a spare LDS region that
+// only profiled launches allocate, and are copied out when the kernel ends, so that recording
+// one costs a clock read and an LDS write (a global store here would be waited for by the next
+// "all loads done" and distort what it measures).
+#define LS_PROF_EVENTS 1024
+#define LS_PROF(tag)                                                                              \
+  do {                                                                                            \
+    if (P.prof != nullptr && (int)blockIdx.x == P.prof_wg && TID == 0 && ms->prof_n < LS_PROF_EVENTS) \
+      reinterpret_cast<unsigned long long*>(ls_smem + LS_SMEM_BYTES)[ms->prof_n++] =              \
+          (wall_clock64() << 8) | (unsigned long long)(tag);                                      \
   } while (0)
 
 struct PassCtx {
@@ -176,24 +218,33 @@ __device__ __forceinline__ Best best_shfl_xor(const Best& a, int mask) {
 // grow: barrier number e completes when the grid counter reaches e * groups.  The caller must
 // have drained its stores (drain_vmem) before; loads issued earlier may still be in flight.
 // The wait is bounded: when it expires the error flag is raised and every workgroup leaves.
-__device__ __forceinline__ bool grid_barrier(const LsKParams& P, Misc* ms) {
-  lds_barrier();
+__device__ __forceinline__ void grid_arrive(const LsKParams& P, Misc* ms) {
+  lds_barrier();   // every wave of this workgroup has drained its stores
   if (TID == 0) {
     const unsigned epoch = ++ms->epoch;
     const unsigned nwg = gridDim.x, wg = blockIdx.x;
     const unsigned ngrp = nwg < 8u ? nwg : 8u;
     const unsigned grp = wg % ngrp;
     const unsigned gsize = (nwg - grp + ngrp - 1) / ngrp;
-    uint32_t* gcnt = P.bar + 64 * (1 + grp);
+    LS_GLOBAL uint32_t* gcnt = (LS_GLOBAL uint32_t*)(P.bar + 64 * (1 + grp));
+    LS_GLOBAL uint32_t* gbar = (LS_GLOBAL uint32_t*)(P.bar);
     const unsigned old = __hip_atomic_fetch_add(gcnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (old == epoch * gsize - 1) __hip_atomic_fetch_add(P.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned target = epoch * ngrp;
+    if (old == epoch * gsize - 1) __hip_atomic_fetch_add(gbar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+__device__ __forceinline__ bool grid_wait(const LsKParams& P, Misc* ms) {
+  if (TID == 0) {
+    const unsigned nwg = gridDim.x;
+    const unsigned ngrp = nwg < 8u ? nwg : 8u;
+    LS_GLOBAL uint32_t* gbar = (LS_GLOBAL uint32_t*)(P.bar);
+    LS_GLOBAL int32_t* gerr = (LS_GLOBAL int32_t*)(&P.state->error);
+    const unsigned target = ms->epoch * ngrp;
     int it = 0;
-    while (__hip_atomic_load(P.bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+    while (__hip_atomic_load(gbar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
       __builtin_amdgcn_s_sleep(1);
       if (++it > P.spin_limit ||
-          ((it & 1023) == 0 && __hip_atomic_load(&P.state->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-        __hip_atomic_store(&P.state->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          ((it & 1023) == 0 && __hip_atomic_load(gerr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+        __hip_atomic_store(gerr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         ms->abort = 1;
         break;
       }
@@ -201,6 +252,12 @@ __device__ __forceinline__ bool grid_barrier(const LsKParams& P, Misc* ms) {
   }
   lds_barrier();
   return ms->abort == 0;
+}
+// Arrival is signalled first; what the caller does between grid_arrive and grid_wait (issuing the
+// next stage's weight loads) overlaps with the other workgroups' arrival.
+__device__ __forceinline__ bool grid_barrier(const LsKParams& P, Misc* ms) {
+  grid_arrive(P, ms);
+  return grid_wait(P, ms);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -211,44 +268,115 @@ struct ActDesc {
   const void* src;   // PLAIN: T[n][ld];  NORM_X: float[n][ld];  NORM_EMB: T embed[vocab][ld]
   int ld;
   const void* gain;  // T[K] RMSNorm gain (NORM modes)
+  const float* ssq;  // NORM_X: per-16-column sums of squares of the rows, [n][ssq_nt]; the first chunk
+  int ssq_nt;        //         turns them into Misc::rinv while the rows themselves are in flight
 };
 
 // Writes rows [0,m) x columns [k0, k0+klen) of the input into LDS as T, 16-byte units swizzled
-// by the row index so that the 16 rows of one unit column hit distinct banks.
-template <typename T>
+// by the row index so that the 16 rows of one unit column hit distinct banks.  Columns at or past
+// K are written as zeros (their loads read column 0 instead, so that no load sits under a branch).
+template <typename T, int MODE>
 __device__ __forceinline__ void stage_act(const ActDesc& A, const Misc* ms, int m, int K, int k0, int klen,
-                                          int rs_units, char* act) {
+                                          int rs_units, char* act, int first = 0) {
   constexpr int EPV = TT<T>::EPV;
   const int upr = klen / EPV;
-  for (int idx = TID; idx < m * upr; idx += LS_THREADS) {
+  for (int idx = first + TID; idx < m * upr; idx += LS_THREADS) {
     const int n = idx / upr, u = idx - n * upr;
     const int k = k0 + u * EPV;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (k < K) {
-      if (A.mode == ACT_PLAIN) {
-        v = ldc128(static_cast<const T*>(A.src) + (size_t)n * A.ld + k);
-      } else {
-        float f[EPV], gn[EPV];
-        if (A.mode == ACT_NORM_X) {
-          const float* s = static_cast<const float*>(A.src) + (size_t)n * A.ld + k;
+    const bool ok = k < K;
+    const int kc = ok ? k : 0;
+    uint4 v;
+    if (MODE == ACT_PLAIN) {
+      v = ldc128(static_cast<const T*>(A.src) + (size_t)n * A.ld + kc);
+    } else {
+      float f[EPV], gn[EPV];
+      if (MODE == ACT_NORM_X) {
+        const float* s = static_cast<const float*>(A.src) + (size_t)n * A.ld + kc;
 #pragma unroll
-          for (int e = 0; e < EPV; e += 2) {
-            const float2 t = ldcf2(s + e);
-            f[e] = t.x; f[e + 1] = t.y;
-          }
-        } else {
-          TT<T>::unpack(*reinterpret_cast<const uint4*>(static_cast<const T*>(A.src) + (size_t)ms->tok[n] * A.ld + k), f);
+        for (int e = 0; e < EPV; e += 2) {
+          const float2 t = ldcf2(s + e);
+          f[e] = t.x; f[e + 1] = t.y;
         }
-        TT<T>::unpack(*reinterpret_cast<const uint4*>(static_cast<const T*>(A.gain) + k), gn);
-        const float r = ms->rinv[n];
-#pragma unroll
-        for (int e = 0; e < EPV; ++e) f[e] = (f[e] * r) * gn[e];
-        v = TT<T>::pack(f);
+      } else {
+        TT<T>::unpack(ldg128(static_cast<const T*>(A.src) + (size_t)ms->tok[n] * A.ld + kc), f);
       }
+      TT<T>::unpack(ldg128(static_cast<const T*>(A.gain) + kc), gn);
+      const float r = ms->rinv[n];
+#pragma unroll
+      for (int e = 0; e < EPV; ++e) f[e] = (f[e] * r) * gn[e];
+      v = TT<T>::pack(f);
     }
+    const uint32_t keep = ok ? 0xFFFFFFFFu : 0u;
+    v = make_uint4(v.x & keep, v.y & keep, v.z & keep, v.w & keep);
     const int pu = (u & ~15) | ((u ^ n) & 15);
     *reinterpret_cast<uint4*>(act + ((size_t)n * rs_units + pu) * 16) = v;
   }
+}
+
+// First chunk of an RMS-normalised input taken from the fp32 residual rows: the per-tile sums of
+// squares and the raw rows are requested together (one memory round trip instead of two), then
+// 1/rms goes to Misc::rinv and the scaled rows to LDS.
+template <typename T>
+__device__ __forceinline__ void stage_act_norm_first(const ActDesc& A, const LsKParams& P, Misc* ms, int m, int K,
+                                                     int klen, int rs_units, char* act) {
+  constexpr int EPV = TT<T>::EPV;
+  constexpr int UMAX = 2;
+  const int lane = LANE, wave = WAVE;
+  const int upr = klen / EPV, total = m * upr;
+  // raw rows first: UMAX units per thread
+  float f[UMAX][EPV];
+  int un[UMAX], uu[UMAX];
+#pragma unroll
+  for (int q = 0; q < UMAX; ++q) {
+    const int idx = TID + q * LS_THREADS;
+    un[q] = idx / upr;
+    uu[q] = idx - un[q] * upr;
+    const bool ok = idx < total && uu[q] * EPV < K;
+    const float* src = static_cast<const float*>(A.src) + (ok ? (size_t)un[q] * A.ld + uu[q] * EPV : 0);
+#pragma unroll
+    for (int e = 0; e < EPV; e += 2) {
+      const float2 t = ldcf2(src + e);
+      f[q][e] = t.x; f[q][e + 1] = t.y;
+    }
+  }
+  // statistics: wave w owns rows w, w+4, ...; lanes run over the 16-column tiles
+  for (int n = wave; n < m; n += 4) {
+    float sacc = 0.f;
+    for (int k0 = 0; k0 < A.ssq_nt; k0 += 256) {
+      float v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int k = k0 + lane + 64 * j;
+        const bool ok = k < A.ssq_nt;
+        const float t = ldcf(A.ssq + (size_t)n * A.ssq_nt + (ok ? k : 0));
+        v[j] = ok ? t : 0.f;
+      }
+      sacc += (v[0] + v[1]) + (v[2] + v[3]);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sacc += __shfl_xor(sacc, o);
+    if (lane == 0) ms->rinv[n] = 1.0f / sqrtf(sacc / (float)P.dm + P.eps);
+  }
+  lds_barrier();
+#pragma unroll
+  for (int q = 0; q < UMAX; ++q) {
+    const int idx = TID + q * LS_THREADS;
+    if (idx < total) {
+      const int n = un[q], u = uu[q], k = u * EPV;
+      const bool ok = k < K;
+      float gn[EPV];
+      TT<T>::unpack(ldg128(static_cast<const T*>(A.gain) + (ok ? k : 0)), gn);
+      const float r = ms->rinv[n];
+#pragma unroll
+      for (int e = 0; e < EPV; ++e) f[q][e] = (f[q][e] * r) * gn[e];
+      uint4 v = TT<T>::pack(f[q]);
+      const uint32_t keep = ok ? 0xFFFFFFFFu : 0u;
+      v = make_uint4(v.x & keep, v.y & keep, v.z & keep, v.w & keep);
+      const int pu = (u & ~15) | ((u ^ n) & 15);
+      *reinterpret_cast<uint4*>(act + ((size_t)n * rs_units + pu) * 16) = v;
+    }
+  }
+  if (total > UMAX * LS_THREADS) stage_act<T, ACT_NORM_X>(A, ms, m, K, 0, klen, rs_units, act, UMAX * LS_THREADS);
 }
 
 // NT weight tiles (16 rows x K each, row-major with leading dimension K) times the staged input.
@@ -256,76 +384,84 @@ __device__ __forceinline__ void stage_act(const ActDesc& A, const Misc* ms, int 
 // begin() issues the first loads (it may be called before a grid barrier: weights do not depend
 // on other workgroups); run() stages the input, multiplies, and leaves the per-wave partial sums
 // in LDS (`act` region) as red[wave][tile][lane]; tile_sum() adds them in wave order.
+// K is walked in whole rounds of 4*DEPTH blocks: blocks past the end multiply clamped (finite)
+// weight loads with zero-filled input, so the loop has no conditional loads.
 template <typename T, int NT, int DEPTH>
 struct Gemm {
   static constexpr int KB = 256 / (int)sizeof(T);
   static constexpr int EPV = TT<T>::EPV;
+  static constexpr int ROUND = 4 * DEPTH;
+  // a chunk of 16 rows must hold at least one round
+  static_assert(LS_ACT_BYTES / (LS_ROWS * 256) >= ROUND, "LDS chunk too small for this prefetch depth");
   uint4 slot[DEPTH][NT][4];
   const T* rp[NT];
   int K, nkb;
 
   __device__ __forceinline__ void load_slot(int s, int kb) {
-    const int g = LANE >> 4;
+    const int e0 = (LANE >> 4) * EPV;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int k = kb * KB + j * (KB / 4) + g * EPV;
-        if (rp[t] != nullptr && k < K)
-          slot[s][t][j] = *reinterpret_cast<const uint4*>(rp[t] + kb * KB + j * (KB / 4));
-        else
-          slot[s][t][j] = make_uint4(0, 0, 0, 0);
+        const int idx = e0 + kb * KB + j * (KB / 4);
+        const int idc = (idx + EPV <= K) ? idx : 0;
+        slot[s][t][j] = ldg128(rp[t] + idc);
       }
     }
   }
 
   __device__ __forceinline__ void begin(const T* const (&wt)[NT], int K_) {
-    const int r = LANE & 15, g = LANE >> 4;
+    const int r = LANE & 15;
     K = K_;
     nkb = (K + KB - 1) / KB;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) rp[t] = wt[t] ? wt[t] + (size_t)r * K + g * EPV : nullptr;
+    for (int t = 0; t < NT; ++t) rp[t] = (wt[t] ? wt[t] : wt[0]) + (size_t)r * K;
 #pragma unroll
     for (int s = 0; s < DEPTH; ++s) load_slot(s, WAVE + 4 * s);
   }
 
-  __device__ __forceinline__ void run(const ActDesc& A, const Misc* ms, int m, char* act) {
+  template <int MODE>
+  __device__ __forceinline__ void run(const ActDesc& A, const LsKParams& P, Misc* ms, int m, char* act) {
     const int lane = LANE, wave = WAVE;
     const int r = lane & 15, g = lane >> 4;
-    int kcb = (LS_ACT_BYTES / (m * 256)) & ~(4 * DEPTH - 1);
-    const int nkb_up = (nkb + 4 * DEPTH - 1) & ~(4 * DEPTH - 1);
-    if (kcb > nkb_up) kcb = nkb_up;
+    const int nkb_pad = (nkb + ROUND - 1) / ROUND * ROUND;
+    int kcb = (LS_ACT_BYTES / (m * 256)) / ROUND * ROUND;
+    if (kcb > nkb_pad) kcb = nkb_pad;
     const int rs_units = kcb * 16;
     f32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int rr = (r < m) ? r : 0;                  // columns past m read row 0 and are masked to zero
+    const uint32_t bmask = (r < m) ? 0xFFFFFFFFu : 0u;
+    const char* brow = act + (size_t)rr * rs_units * 16;
 
     lds_barrier();  // the previous user of the LDS region is done with it
-    for (int c0 = 0; c0 < nkb; c0 += kcb) {
+    for (int c0 = 0; c0 < nkb_pad; c0 += kcb) {
+      const int clen = (c0 + kcb <= nkb_pad) ? kcb : nkb_pad - c0;
       if (c0) lds_barrier();
-      const int cend = (c0 + kcb < nkb) ? c0 + kcb : nkb;
-      stage_act<T>(A, ms, m, K, c0 * KB, (cend - c0) * KB, rs_units, act);
+      if (MODE == ACT_NORM_X && c0 == 0 && A.ssq != nullptr)
+        stage_act_norm_first<T>(A, P, ms, m, K, clen * KB, rs_units, act);
+      else
+        stage_act<T, MODE>(A, ms, m, K, c0 * KB, clen * KB, rs_units, act);
       lds_barrier();
-      for (int kb0 = c0 + wave; kb0 < cend; kb0 += 4 * DEPTH) {
+      for (int kb0 = wave; kb0 < clen; kb0 += ROUND) {
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
-          const int kb = kb0 + 4 * s;
-          if (kb < cend) {
-            uint4 b[4];
+          const int kbl = kb0 + 4 * s;   // block within the chunk
+          uint4 b[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const int u = (kb - c0) * 16 + j * 4 + g;
-              const int pu = (u & ~15) | ((u ^ r) & 15);
-              b[j] = (r < m) ? *reinterpret_cast<const uint4*>(act + ((size_t)r * rs_units + pu) * 16)
-                             : make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-#pragma unroll
-              for (int j = 0; j < 4; ++j) TT<T>::mma(acc[t], slot[s][t][j], b[j]);
-            }
-            load_slot(s, kb + 4 * DEPTH);
+          for (int j = 0; j < 4; ++j) {
+            const int u = kbl * 16 + j * 4 + g;
+            const int pu = (u & ~15) | ((u ^ rr) & 15);
+            const uint4 bv = *reinterpret_cast<const uint4*>(brow + (size_t)pu * 16);
+            b[j] = make_uint4(bmask & bv.x, bmask & bv.y, bmask & bv.z, bmask & bv.w);
           }
+#pragma unroll
+          for (int t = 0; t < NT; ++t) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) TT<T>::mma(acc[t], slot[s][t][j], b[j]);
+          }
+          load_slot(s, c0 + kbl + ROUND);
         }
       }
     }
@@ -374,10 +510,11 @@ __device__ __forceinline__ void compute_rinv(const LsKParams& P, const PassCtx& 
 // Stage A: RMSNorm + QKV projection + RoPE + KV append.  A work item is a pair of 16-row tiles:
 // for q and k the rows (j, j + hd/2) that one rotation mixes, for v two adjacent tiles.
 template <typename T, int NT>
-__device__ __noinline__ bool stage_qkv(const LsKParams& P, const PassCtx& pc, int l, Misc* ms, char* act) {
-  constexpr int DEPTH = (NT == 4) ? 2 : 4;
+__device__ __forceinline__ bool stage_qkv(const PassCtx pc, int l) {
+  LS_CTX;
+  constexpr int DEPTH = 4 / NT;
   constexpr int IPG = NT / 2;
-  const LsLayerW& W = P.layers[l];
+  const LsLayerW W = layer_w(P, ms, l);
   const int hd = P.hd, dm = P.dm, half = hd / 2;
   const int pph = hd / 32;
   const int nq_items = P.nq * pph, nk_items = P.nkv * pph, nv_items = P.kvd / 32;
@@ -389,6 +526,8 @@ __device__ __noinline__ bool stage_qkv(const LsKParams& P, const PassCtx& pc, in
   A.src = emb ? P.embed : static_cast<const void*>(P.xbuf + (size_t)pc.row0 * dm);
   A.ld = dm;
   A.gain = W.attn_norm;
+  A.ssq = emb ? nullptr : P.ssq + (size_t)pc.row0 * (dm / 16);
+  A.ssq_nt = dm / 16;
   const int lane = LANE, wave = WAVE, n = lane & 15, g = lane >> 4;
   auto tiles_of = [&](int grp, const T* (&wt)[NT]) {
 #pragma unroll
@@ -416,15 +555,17 @@ __device__ __noinline__ bool stage_qkv(const LsKParams& P, const PassCtx& pc, in
   const T* wt[NT];
   int grp = blockIdx.x;
   LS_PROF(0x10);
+  grid_arrive(P, ms);
   if (grp < groups) { tiles_of(grp, wt); G.begin(wt, dm); }
   LS_PROF(0x11);
-  if (!grid_barrier(P, ms)) return false;
+  if (!grid_wait(P, ms)) return false;
   LS_PROF(0x12);
-  compute_rinv<T>(P, pc, emb, ms);
+  if (emb) compute_rinv<T>(P, pc, true, ms);
   LS_PROF(0x13);
   for (; grp < groups; grp += gridDim.x) {
     if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, dm); }
-    G.run(A, ms, pc.m, act);
+    if (emb) G.template run<ACT_NORM_EMB>(A, P, ms, pc.m, act);
+    else G.template run<ACT_NORM_X>(A, P, ms, pc.m, act);
     LS_PROF(0x14);
     if (wave < IPG) {
       const int item = grp * IPG + wave;
@@ -442,7 +583,7 @@ __device__ __noinline__ bool stage_qkv(const LsKParams& P, const PassCtx& pc, in
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
               const int dj = jb * 16 + 4 * g + j;
-              const float c = P.rope_cos[(size_t)pos * half + dj], s = P.rope_sin[(size_t)pos * half + dj];
+              const float c = ldgf(P.rope_cos + (size_t)pos * half + dj), s = ldgf(P.rope_sin + (size_t)pos * half + dj);
               lo[j] = a[j] * c - b[j] * s;
               hi[j] = b[j] * c + a[j] * s;
             }
@@ -472,7 +613,8 @@ __device__ __noinline__ bool stage_qkv(const LsKParams& P, const PassCtx& pc, in
 // A work item is (kv head, 64-position tile); the last workgroup to finish a kv head merges the
 // per-tile partial softmaxes in tile order.
 template <typename T, int HD>
-__device__ __noinline__ bool stage_attn(const LsKParams& P, const PassCtx& pc, int l, Misc* ms, char* act) {
+__device__ __forceinline__ bool stage_attn(const PassCtx pc, int l) {
+  LS_CTX;
   constexpr int TP = LS_ATTN_TILE;
   constexpr int SEG = HD / 4;           // dims per thread in the q.k product
   constexpr int DQ = HD / 4;            // threads across one V row (4 dims each)
@@ -502,25 +644,23 @@ __device__ __noinline__ bool stage_attn(const LsKParams& P, const PassCtx& pc, i
     // K: thread (key u, segment seg); V: thread (dim quad dq, key part)
     const int u = tid >> 2, seg = tid & 3;
     float kreg[SEG];
-    if (u < nvalid) {
-      const T* kp = kc + ((size_t)c * P.max_seq + kp0 + u) * HD + seg * SEG;
+    {
+      const bool ok = u < nvalid;   // keys past the end read key 0 of the tile and are zeroed
+      const T* kp = kc + ((size_t)c * P.max_seq + kp0 + (ok ? u : 0)) * HD + seg * SEG;
 #pragma unroll
       for (int e = 0; e < SEG; e += 4) TT<T>::ldc4(kp + e, &kreg[e]);
-    } else {
 #pragma unroll
-      for (int e = 0; e < SEG; ++e) kreg[e] = 0.f;
+      for (int e = 0; e < SEG; ++e) kreg[e] = ok ? kreg[e] : 0.f;
     }
     const int dq = tid % DQ, part = tid / DQ;
     float vreg[KPP][4];
 #pragma unroll
     for (int kk = 0; kk < KPP; ++kk) {
       const int key = part * KPP + kk;
-      if (key < nvalid) {
-        TT<T>::ldc4(vc + ((size_t)c * P.max_seq + kp0 + key) * HD + dq * 4, vreg[kk]);
-      } else {
+      const bool ok = key < nvalid;
+      TT<T>::ldc4(vc + ((size_t)c * P.max_seq + kp0 + (ok ? key : 0)) * HD + dq * 4, vreg[kk]);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) vreg[kk][e] = 0.f;
-      }
+      for (int e = 0; e < 4; ++e) vreg[kk][e] = ok ? vreg[kk][e] : 0.f;
     }
     float* pout = P.attn_part + ((size_t)(c * P.max_tiles + ti) * 64) * PSTRIDE;
 
@@ -595,30 +735,63 @@ __device__ __noinline__ bool stage_attn(const LsKParams& P, const PassCtx& pc, i
     drain_vmem();
     lds_barrier();
     if (tid == 0) {
-      const unsigned old = __hip_atomic_fetch_add(P.attn_cnt + c, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned old = __hip_atomic_fetch_add((LS_GLOBAL uint32_t*)(P.attn_cnt + c), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       ms->flag = (old == (unsigned)(ntiles - 1));
     }
     lds_barrier();
     if (ms->flag) {
       const float* pin = P.attn_part + ((size_t)(c * P.max_tiles) * 64) * PSTRIDE;
-      for (int idx = tid; idx < nQ * (HD / 2); idx += LS_THREADS) {
-        const int qg = idx / (HD / 2), dim = (idx - qg * (HD / 2)) * 2;
-        float M = -INFINITY;
-        for (int t = 0; t < ntiles; ++t) M = fmaxf(M, ldcf(pin + ((size_t)t * 64 + qg) * PSTRIDE + HD));
-        float n0 = 0.f, n1 = 0.f, den = 0.f;
-        for (int t = 0; t < ntiles; ++t) {
-          const float* pp = pin + ((size_t)t * 64 + qg) * PSTRIDE;
-          const float2 stt = ldcf2(pp + HD);
-          const float2 ov = ldcf2(pp + dim);
-          const float w = (stt.x == -INFINITY) ? 0.f : expf(stt.x - M);
-          n0 += w * ov.x;
-          n1 += w * ov.y;
-          den += w * stt.y;
+      float* wts = reinterpret_cast<float*>(act);   // [16][ntiles] softmax weights of the tiles
+      float* dens = wts + 16 * ntiles;              // [16]
+      for (int qb = 0; qb < nQ; qb += 16) {
+        const int nqb = (nQ - qb < 16) ? nQ - qb : 16;
+        lds_barrier();
+        for (int qi = wave; qi < nqb; qi += 4) {
+          const int qg = qb + qi;
+          float M = -INFINITY;
+          for (int t = lane; t < ntiles; t += 64) M = fmaxf(M, ldcf(pin + ((size_t)t * 64 + qg) * PSTRIDE + HD));
+#pragma unroll
+          for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+          float den = 0.f;
+          for (int t0 = 0; t0 < ntiles; t0 += 64) {
+            const int t = t0 + lane;
+            float w = 0.f, l = 0.f;
+            if (t < ntiles) {
+              const float2 stt = ldcf2(pin + ((size_t)t * 64 + qg) * PSTRIDE + HD);
+              w = (stt.x == -INFINITY) ? 0.f : expf(stt.x - M);
+              l = stt.y;
+              wts[qi * ntiles + t] = w;
+            }
+            float part = w * l;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
+            den += part;
+          }
+          if (lane == 0) dens[qi] = den;
         }
-        const int n = qg / G, gq = qg - n * G;
-        TT<T>::stc2(static_cast<T*>(P.obuf) + (size_t)n * P.qd + (c * G + gq) * HD + dim, n0 / den, n1 / den);
+        lds_barrier();
+        for (int idx = tid; idx < nqb * (HD / 2); idx += LS_THREADS) {
+          const int qi = idx / (HD / 2), dim = (idx - qi * (HD / 2)) * 2;
+          const int qg = qb + qi;
+          float n0 = 0.f, n1 = 0.f;
+          for (int t0 = 0; t0 < ntiles; t0 += 8) {
+            float2 ov[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+              ov[j] = ldcf2(pin + ((size_t)((t0 + j < ntiles) ? t0 + j : 0) * 64 + qg) * PSTRIDE + dim);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              const float w = (t0 + j < ntiles) ? wts[qi * ntiles + t0 + j] : 0.f;
+              n0 += w * ov[j].x;
+              n1 += w * ov[j].y;
+            }
+          }
+          const float den = dens[qi];
+          const int n = qg / G, gq = qg - n * G;
+          TT<T>::stc2(static_cast<T*>(P.obuf) + (size_t)n * P.qd + (c * G + gq) * HD + dim, n0 / den, n1 / den);
+        }
       }
-      if (tid == 0) __hip_atomic_store(P.attn_cnt + c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (tid == 0) stc32(P.attn_cnt + c, 0u);
     }
   }
   LS_PROF(0x25);
@@ -631,9 +804,10 @@ __device__ __noinline__ bool stage_attn(const LsKParams& P, const PassCtx& pc, i
 // Stages C and E: x += W * in  (O projection of the attention output; down projection of the
 // SwiGLU output), plus the per-tile sums of squares the next RMSNorm needs.
 template <typename T, int NT>
-__device__ __noinline__ bool stage_resid(const LsKParams& P, const PassCtx& pc, int l, bool is_down, Misc* ms, char* act) {
-  constexpr int DEPTH = (NT == 4) ? 2 : 4;
-  const LsLayerW& W = P.layers[l];
+__device__ __forceinline__ bool stage_resid(const PassCtx pc, int l, bool is_down) {
+  LS_CTX;
+  constexpr int DEPTH = 4 / NT;
+  const LsLayerW W = layer_w(P, ms, l);
   const int dm = P.dm;
   const int K = is_down ? P.ffn : P.qd;
   const T* wmat = static_cast<const T*>(is_down ? W.wd : W.wo);
@@ -644,6 +818,8 @@ __device__ __noinline__ bool stage_resid(const LsKParams& P, const PassCtx& pc, 
   A.src = is_down ? P.actbuf : P.obuf;
   A.ld = K;
   A.gain = nullptr;
+  A.ssq = nullptr;
+  A.ssq_nt = 0;
   const bool emb = !is_down && pc.embed_src && l == pc.l0;  // residual comes from the embedding row
   const int lane = LANE, wave = WAVE, n = lane & 15, g = lane >> 4;
   auto tiles_of = [&](int grp, const T* (&wt)[NT]) {
@@ -657,13 +833,29 @@ __device__ __noinline__ bool stage_resid(const LsKParams& P, const PassCtx& pc, 
   const T* wt[NT];
   int grp = blockIdx.x;
   LS_PROF(is_down ? 0x50 : 0x30);
+  grid_arrive(P, ms);
   if (grp < groups) { tiles_of(grp, wt); G.begin(wt, K); }
+  // residual values of this workgroup's first tiles: written at least one barrier ago, so they can
+  // be requested ahead of this stage's barrier
+  float xres[4] = {0.f, 0.f, 0.f, 0.f};
+  if (grp < groups && wave < NT && grp * NT + wave < tiles && n < pc.m) {
+    const int row = (grp * NT + wave) * 16 + 4 * g;
+    if (emb) {
+      const T* e = static_cast<const T*>(P.embed) + (size_t)ms->tok[n] * dm + row;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) xres[j] = TT<T>::ld(e + j);
+    } else {
+      const float* xr = P.xbuf + (size_t)(pc.row0 + n) * dm + row;
+      const float2 o0 = ldcf2(xr), o1 = ldcf2(xr + 2);
+      xres[0] = o0.x; xres[1] = o0.y; xres[2] = o1.x; xres[3] = o1.y;
+    }
+  }
   LS_PROF(is_down ? 0x51 : 0x31);
-  if (!grid_barrier(P, ms)) return false;
+  if (!grid_wait(P, ms)) return false;
   LS_PROF(is_down ? 0x52 : 0x32);
   for (; grp < groups; grp += gridDim.x) {
     if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, K); }
-    G.run(A, ms, pc.m, act);
+    G.template run<ACT_PLAIN>(A, P, ms, pc.m, act);
     LS_PROF(is_down ? 0x54 : 0x34);
     for (int t = wave; t < NT; t += 4) {
       const int tile = grp * NT + t;
@@ -673,7 +865,10 @@ __device__ __noinline__ bool stage_resid(const LsKParams& P, const PassCtx& pc, 
       float nx[4] = {0.f, 0.f, 0.f, 0.f};
       if (n < pc.m) {
         float* xr = P.xbuf + (size_t)(pc.row0 + n) * dm + row;
-        if (emb) {
+        if (grp == (int)blockIdx.x) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) nx[j] = xres[j] + v[j];
+        } else if (emb) {
           const T* e = static_cast<const T*>(P.embed) + (size_t)ms->tok[n] * dm + row;
 #pragma unroll
           for (int j = 0; j < 4; ++j) nx[j] = TT<T>::ld(e + j) + v[j];
@@ -684,8 +879,7 @@ __device__ __noinline__ bool stage_resid(const LsKParams& P, const PassCtx& pc, 
         stcf2(xr, nx[0], nx[1]);
         stcf2(xr + 2, nx[2], nx[3]);
         if (is_down && P.capture != nullptr)
-          *reinterpret_cast<float4*>(P.capture + ((size_t)l * P.max_seq + pc.pos0 + n) * dm + row) =
-              make_float4(nx[0], nx[1], nx[2], nx[3]);
+          stg128(P.capture + ((size_t)l * P.max_seq + pc.pos0 + n) * dm + row, make_float4(nx[0], nx[1], nx[2], nx[3]));
       }
       float s = nx[0] * nx[0] + nx[1] * nx[1] + nx[2] * nx[2] + nx[3] * nx[3];
       s += __shfl_xor(s, 16);
@@ -703,10 +897,11 @@ __device__ __noinline__ bool stage_resid(const LsKParams& P, const PassCtx& pc, 
 // Stage D: RMSNorm + gate/up projection + SwiGLU.  A work item pairs the gate tile and the up
 // tile of the same 16 features.
 template <typename T, int NT>
-__device__ __noinline__ bool stage_gu(const LsKParams& P, const PassCtx& pc, int l, Misc* ms, char* act) {
-  constexpr int DEPTH = (NT == 4) ? 2 : 4;
+__device__ __forceinline__ bool stage_gu(const PassCtx pc, int l) {
+  LS_CTX;
+  constexpr int DEPTH = 4 / NT;
   constexpr int IPG = NT / 2;
-  const LsLayerW& W = P.layers[l];
+  const LsLayerW W = layer_w(P, ms, l);
   const int dm = P.dm;
   const int items = P.ffn / 16;
   const int groups = (items + IPG - 1) / IPG;
@@ -715,6 +910,8 @@ __device__ __noinline__ bool stage_gu(const LsKParams& P, const PassCtx& pc, int
   A.src = P.xbuf + (size_t)pc.row0 * dm;
   A.ld = dm;
   A.gain = W.ffn_norm;
+  A.ssq = P.ssq + (size_t)pc.row0 * (dm / 16);
+  A.ssq_nt = dm / 16;
   const int lane = LANE, wave = WAVE, n = lane & 15, g = lane >> 4;
   auto tiles_of = [&](int grp, const T* (&wt)[NT]) {
 #pragma unroll
@@ -728,15 +925,15 @@ __device__ __noinline__ bool stage_gu(const LsKParams& P, const PassCtx& pc, int
   const T* wt[NT];
   int grp = blockIdx.x;
   LS_PROF(0x40);
+  grid_arrive(P, ms);
   if (grp < groups) { tiles_of(grp, wt); G.begin(wt, dm); }
   LS_PROF(0x41);
-  if (!grid_barrier(P, ms)) return false;
+  if (!grid_wait(P, ms)) return false;
   LS_PROF(0x42);
-  compute_rinv<T>(P, pc, false, ms);
   LS_PROF(0x43);
   for (; grp < groups; grp += gridDim.x) {
     if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, dm); }
-    G.run(A, ms, pc.m, act);
+    G.template run<ACT_NORM_X>(A, P, ms, pc.m, act);
     LS_PROF(0x44);
     if (wave < IPG) {
       const int item = grp * IPG + wave;
@@ -762,8 +959,9 @@ __device__ __noinline__ bool stage_gu(const LsKParams& P, const PassCtx& pc, int
 // Head: final RMSNorm + LM head + per-row argmax (highest value, lowest index on ties) with the
 // runner-up value kept for the margin.  Each workgroup writes one candidate per row.
 template <typename T>
-__device__ __noinline__ bool stage_head(const LsKParams& P, const PassCtx& pc, Misc* ms, char* act) {
-  constexpr int NT = 4, DEPTH = 2;
+__device__ __noinline__ bool stage_head(const PassCtx pc) {
+  LS_CTX;
+  constexpr int NT = 2, DEPTH = 2;
   const int dm = P.dm;
   const int tiles = P.vocab / 16;
   const int groups = (tiles + NT - 1) / NT;
@@ -772,6 +970,8 @@ __device__ __noinline__ bool stage_head(const LsKParams& P, const PassCtx& pc, M
   A.src = P.xbuf + (size_t)pc.row0 * dm;
   A.ld = dm;
   A.gain = P.final_norm;
+  A.ssq = P.ssq + (size_t)pc.row0 * (dm / 16);
+  A.ssq_nt = dm / 16;
   const int lane = LANE, wave = WAVE, n = lane & 15, g = lane >> 4;
   auto tiles_of = [&](int grp, const T* (&wt)[NT]) {
 #pragma unroll
@@ -786,18 +986,18 @@ __device__ __noinline__ bool stage_head(const LsKParams& P, const PassCtx& pc, M
   const T* wt[NT];
   int grp = blockIdx.x;
   LS_PROF(0x60);
+  grid_arrive(P, ms);
   if (grp < groups) { tiles_of(grp, wt); G.begin(wt, dm); }
   LS_PROF(0x61);
-  if (!grid_barrier(P, ms)) return false;
+  if (!grid_wait(P, ms)) return false;
   LS_PROF(0x62);
-  compute_rinv<T>(P, pc, false, ms);
   LS_PROF(0x63);
   for (; grp < groups; grp += gridDim.x) {
     if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, dm); }
-    G.run(A, ms, pc.m, act);
+    G.template run<ACT_NORM_X>(A, P, ms, pc.m, act);
     LS_PROF(0x64);
     const int tile = grp * NT + wave;
-    if (tile < tiles) {
+    if (wave < NT && tile < tiles) {
       const f32x4 v = tile_sum<NT>(act, wave);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -826,7 +1026,8 @@ __device__ __noinline__ bool stage_head(const LsKParams& P, const PassCtx& pc, M
 }
 
 // After the head stage: every workgroup merges all candidates (same result everywhere).
-__device__ __noinline__ bool reduce_cands(const LsKParams& P, const PassCtx& pc, Misc* ms) {
+__device__ __noinline__ bool reduce_cands(const PassCtx pc) {
+  LS_CTX;
   LS_PROF(0x70);
   if (!grid_barrier(P, ms)) return false;
   LS_PROF(0x72);
@@ -860,29 +1061,37 @@ __device__ __noinline__ bool reduce_cands(const LsKParams& P, const PassCtx& pc,
 }
 
 // ------------------------------------------------------------------------------------------
+// One decoder layer for the rows of a pass.  The five stages are inlined into ONE function per
+// (dtype, head_dim, tiles-per-group) so that the call overhead (saving and restoring the callee-
+// saved registers of a 250-register function) is paid once per layer, not once per stage.
+template <typename T, int HD, int NTO>
+__device__ __noinline__ bool layer_pass(const PassCtx pc, int l) {
+  if (!stage_qkv<T, 2>(pc, l)) return false;
+  if (!stage_attn<T, HD>(pc, l)) return false;
+  if (!stage_resid<T, NTO>(pc, l, false)) return false;
+  if (!stage_gu<T, 2>(pc, l)) return false;
+  return stage_resid<T, NTO>(pc, l, true);
+}
+
 // One pass.  Every stage starts with the grid barrier that orders it after the stage before
 // (weight loads for its first tiles are issued ahead of that barrier).
 template <typename T>
-__device__ bool run_pass(const LsKParams& P, const PassCtx& pc, Misc* ms, char* act) {
+__device__ __forceinline__ bool run_pass(const PassCtx& pc) {
+  LS_CTX;
+  const int variant = (P.hd == 128 ? 2 : 0) | (P.nt_o == 2 ? 1 : 0);
   for (int l = pc.l0; l < pc.l1; ++l) {
-    bool ok = (P.nt_qkv == 4) ? stage_qkv<T, 4>(P, pc, l, ms, act) : stage_qkv<T, 2>(P, pc, l, ms, act);
-    if (!ok) return false;
-    ok = (P.hd == 128) ? stage_attn<T, 128>(P, pc, l, ms, act) : stage_attn<T, 64>(P, pc, l, ms, act);
-    if (!ok) return false;
-    ok = (P.nt_o == 4) ? stage_resid<T, 4>(P, pc, l, false, ms, act)
-       : (P.nt_o == 2) ? stage_resid<T, 2>(P, pc, l, false, ms, act)
-                       : stage_resid<T, 1>(P, pc, l, false, ms, act);
-    if (!ok) return false;
-    ok = (P.nt_gu == 4) ? stage_gu<T, 4>(P, pc, l, ms, act) : stage_gu<T, 2>(P, pc, l, ms, act);
-    if (!ok) return false;
-    ok = (P.nt_down == 4) ? stage_resid<T, 4>(P, pc, l, true, ms, act)
-       : (P.nt_down == 2) ? stage_resid<T, 2>(P, pc, l, true, ms, act)
-                          : stage_resid<T, 1>(P, pc, l, true, ms, act);
+    bool ok;
+    switch (variant) {
+      case 0: ok = layer_pass<T, 64, 1>(pc, l); break;
+      case 1: ok = layer_pass<T, 64, 2>(pc, l); break;
+      case 2: ok = layer_pass<T, 128, 1>(pc, l); break;
+      default: ok = layer_pass<T, 128, 2>(pc, l); break;
+    }
     if (!ok) return false;
   }
   if (pc.head) {
-    if (!stage_head<T>(P, pc, ms, act)) return false;
-    if (!reduce_cands(P, pc, ms)) return false;
+    if (!stage_head<T>(pc)) return false;
+    if (!reduce_cands(pc)) return false;
   }
   return true;
 }
@@ -891,14 +1100,15 @@ __device__ __forceinline__ int clamp_tok(int t, int vocab) { return t < 0 ? 0 : 
 
 // Self-drafting (Section 4.3.1) followed by the early-layer pass for the last draft.
 template <typename T>
-__device__ bool do_draft(const LsKParams& P, int E, int d, Misc* ms, char* act) {
+__device__ __forceinline__ bool do_draft(int E, int d) {
+  LS_CTX;
   PassCtx pc;
   pc.m = 1; pc.l0 = 0; pc.l1 = E; pc.embed_src = true;
   for (int i = 0; i <= d; ++i) {
     if (TID == 0) ms->tok[0] = clamp_tok(i == 0 ? ms->st.last : ms->st.D[i - 1], P.vocab);
     __syncthreads();
     pc.row0 = i; pc.pos0 = ms->st.pos + i; pc.head = i < d;
-    if (!run_pass<T>(P, pc, ms, act)) return false;
+    if (!run_pass<T>(pc)) return false;
     if (i < d && TID == 0) { ms->st.D[i] = ms->r_tok[0]; ms->st.dmargin[i] = ms->r_margin[0]; }
     __syncthreads();
   }
@@ -909,10 +1119,11 @@ __device__ bool do_draft(const LsKParams& P, int E, int d, Misc* ms, char* act) 
 
 // Self-verification (Section 4.3.2), acceptance and cache crop (Appendix A.4).
 template <typename T>
-__device__ bool do_verify(const LsKParams& P, int E, int d, Misc* ms, char* act) {
+__device__ __forceinline__ bool do_verify(int E, int d) {
+  LS_CTX;
   PassCtx pc;
   pc.m = d + 1; pc.row0 = 0; pc.pos0 = ms->st.pos; pc.l0 = E; pc.l1 = P.L; pc.embed_src = false; pc.head = true;
-  if (!run_pass<T>(P, pc, ms, act)) return false;
+  if (!run_pass<T>(pc)) return false;
   if (TID == 0) {
     LsState& st = ms->st;
     for (int i = 0; i <= d; ++i) { st.V[i] = ms->r_tok[i]; st.vmargin[i] = ms->r_margin[i]; }
@@ -942,10 +1153,16 @@ __device__ bool do_verify(const LsKParams& P, int E, int d, Misc* ms, char* act)
 }
 
 template <typename T>
-__device__ __forceinline__ void program_body(const LsKParams& P) {
-  extern __shared__ __align__(16) char smem[];
-  char* act = smem;
-  Misc* ms = reinterpret_cast<Misc*>(smem + LS_ACT_BYTES);
+__device__ __forceinline__ void program_body(const LsKParams& Pk) {
+  {
+    Misc* const m0 = MS();
+    if (TID == 0) m0->P = Pk;
+    const int nptr = (Pk.L < LS_LDS_LAYERS ? Pk.L : LS_LDS_LAYERS) * (int)(sizeof(LsLayerW) / sizeof(void*));
+    for (int i = TID; i < nptr; i += LS_THREADS)
+      reinterpret_cast<const void**>(m0->lw)[i] = reinterpret_cast<const void* const*>(Pk.layers)[i];
+    __syncthreads();
+  }
+  LS_CTX;
   if (TID == 0) {
     ms->st = *P.state;
     ms->epoch = 0;
@@ -965,7 +1182,7 @@ __device__ __forceinline__ void program_body(const LsKParams& P) {
       pc.head = (P.kind == LS_PROG_SCORE) || (c0 + LS_ROWS >= n);
       if (TID < pc.m) ms->tok[TID] = clamp_tok(P.tokens[c0 + TID], P.vocab);
       __syncthreads();
-      ok = run_pass<T>(P, pc, ms, act);
+      ok = run_pass<T>(pc);
       if (!ok) break;
       if (P.kind == LS_PROG_SCORE && blockIdx.x == 0 && TID < pc.m) {
         P.out_tokens[c0 + TID] = ms->r_tok[TID];
@@ -990,10 +1207,10 @@ __device__ __forceinline__ void program_body(const LsKParams& P) {
       if (TID == 0) ms->st.error = 2;
       __syncthreads();
     } else {
-      ok = do_draft<T>(P, P.E, P.d, ms, act);
+      ok = do_draft<T>(P.E, P.d);
     }
   } else if (P.kind == LS_PROG_VERIFY) {
-    if (ms->st.draft_valid && ms->st.draft_E == P.E && ms->st.draft_d == P.d) ok = do_verify<T>(P, P.E, P.d, ms, act);
+    if (ms->st.draft_valid && ms->st.draft_E == P.E && ms->st.draft_d == P.d) ok = do_verify<T>(P.E, P.d);
   } else if (P.kind == LS_PROG_GENERATE) {
     while (ok && !ms->st.done && ms->st.n_gen < P.max_new) {
       if (ms->st.pos + P.d + 1 > P.max_seq) {
@@ -1002,14 +1219,14 @@ __device__ __forceinline__ void program_body(const LsKParams& P) {
         break;
       }
       if (P.d > 0) {
-        ok = do_draft<T>(P, P.E, P.d, ms, act);
-        if (ok) ok = do_verify<T>(P, P.E, P.d, ms, act);
+        ok = do_draft<T>(P.E, P.d);
+        if (ok) ok = do_verify<T>(P.E, P.d);
       } else {
         PassCtx pc;
         pc.m = 1; pc.row0 = 0; pc.pos0 = ms->st.pos; pc.l0 = 0; pc.l1 = P.layers_used; pc.embed_src = true; pc.head = true;
         if (TID == 0) ms->tok[0] = clamp_tok(ms->st.last, P.vocab);
         __syncthreads();
-        ok = run_pass<T>(P, pc, ms, act);
+        ok = run_pass<T>(pc);
         if (ok && TID == 0) {
           LsState& st = ms->st;
           const int tok = ms->r_tok[0];
@@ -1021,6 +1238,12 @@ __device__ __forceinline__ void program_body(const LsKParams& P) {
         __syncthreads();
       }
     }
+  }
+  if (P.prof != nullptr && (int)blockIdx.x == P.prof_wg) {
+    __syncthreads();
+    const int nev = ms->prof_n < P.prof_cap ? ms->prof_n : P.prof_cap;
+    for (int i = TID; i < nev; i += LS_THREADS)
+      P.prof[i] = reinterpret_cast<const unsigned long long*>(ls_smem + LS_SMEM_BYTES)[i];
   }
   if (ok && blockIdx.x == 0 && TID == 0) {
     const int dev_err = P.state->error;
@@ -1051,10 +1274,11 @@ extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid
   // The grid is sized to be co-resident (occupancy x compute units) and the barrier wait is bounded,
   // so an ordinary launch is used; LS_COOPERATIVE_LAUNCH=1 asks the runtime to guarantee residency.
   static const bool coop = []() { const char* v = getenv("LS_COOPERATIVE_LAUNCH"); return v != nullptr && v[0] == '1'; }();
+  const size_t smem = LS_SMEM_BYTES + (p->prof != nullptr ? LS_PROF_EVENTS * 8 : 0);
   hipError_t e = coop ? hipLaunchCooperativeKernel(kernel_for(p->kind, dtype_is_bf16), dim3(grid), dim3(LS_THREADS),
-                                                   args, LS_SMEM_BYTES, stream)
+                                                   args, smem, stream)
                       : hipLaunchKernel(kernel_for(p->kind, dtype_is_bf16), dim3(grid), dim3(LS_THREADS), args,
-                                        LS_SMEM_BYTES, stream);
+                                        smem, stream);
   return e == hipSuccess ? 0 : (int)e;
 }
 
@@ -1062,10 +1286,10 @@ extern "C" int ls_kernel_setup(int dtype_is_bf16, int* max_blocks_per_cu) {
   int nb_min = 1 << 30;
   for (int kind : {(int)LS_PROG_PREFILL, (int)LS_PROG_GENERATE}) {
     const void* fn = kernel_for(kind, dtype_is_bf16);
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LS_SMEM_BYTES);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LS_SMEM_BYTES + LS_PROF_EVENTS * 8);
     if (e != hipSuccess) return (int)e;
     int nb = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, LS_THREADS, LS_SMEM_BYTES);
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, LS_THREADS, LS_SMEM_BYTES + LS_PROF_EVENTS * 8);
     if (e != hipSuccess) return (int)e;
     if (nb < nb_min) nb_min = nb;
   }
