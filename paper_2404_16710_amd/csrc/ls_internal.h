@@ -6,10 +6,11 @@
 #include <stddef.h>
 
 #define LS_THREADS 256          // workgroup size of the persistent kernel (4 wavefronts)
+#define LS_WAVES (LS_THREADS / 64)
 #define LS_ROWS 16              // rows per pass (MFMA N dimension)
 #define LS_ATTN_TILE 64         // KV positions per attention work item
 #define LS_ACT_BYTES (64 * 1024) // LDS bytes for staged matmul inputs
-#define LS_MISC_BYTES 8192       // LDS bytes for state, statistics and small scratch
+#define LS_MISC_BYTES 6656       // LDS bytes for state, statistics and small scratch
 #define LS_SMEM_BYTES (LS_ACT_BYTES + LS_MISC_BYTES)
 
 struct LsLayerW {

@@ -151,7 +151,7 @@ struct Misc {
   float rinv[LS_ROWS];
   int r_tok[LS_ROWS];
   float r_margin[LS_ROWS];
-  Best wb[4][LS_ROWS];
+  Best wb[LS_WAVES][LS_ROWS];
   unsigned epoch;
   int flag;
   int abort;
@@ -182,7 +182,7 @@ __device__ __forceinline__ LsLayerW layer_w(const LsKParams& P, const Misc* ms, 
 // only profiled launches allocate, and are copied out when the kernel ends, so that recording
 // one costs a clock read and an LDS write (a global store here would be waited for by the next
 // "all loads done" and distort what it measures).
-#define LS_PROF_EVENTS 1024
+#define LS_PROF_EVENTS 512
 #define LS_PROF(tag)                                                                              \
   do {                                                                                            \
     if (P.prof != nullptr && (int)blockIdx.x == P.prof_wg && TID == 0 && ms->prof_n < LS_PROF_EVENTS) \
@@ -340,7 +340,7 @@ __device__ __forceinline__ void stage_act_norm_first(const ActDesc& A, const LsK
     }
   }
   // statistics: wave w owns rows w, w+4, ...; lanes run over the 16-column tiles
-  for (int n = wave; n < m; n += 4) {
+  for (int n = wave; n < m; n += LS_WAVES) {
     float sacc = 0.f;
     for (int k0 = 0; k0 < A.ssq_nt; k0 += 256) {
       float v[4];
@@ -380,17 +380,18 @@ __device__ __forceinline__ void stage_act_norm_first(const ActDesc& A, const LsK
 }
 
 // NT weight tiles (16 rows x K each, row-major with leading dimension K) times the staged input.
-// The 4 waves take every 4th 256-byte block of K; DEPTH blocks per wave are kept in flight.
+// The waves of the workgroup take the 256-byte blocks of K round-robin; DEPTH blocks per wave are
+// kept in flight.
 // begin() issues the first loads (it may be called before a grid barrier: weights do not depend
 // on other workgroups); run() stages the input, multiplies, and leaves the per-wave partial sums
 // in LDS (`act` region) as red[wave][tile][lane]; tile_sum() adds them in wave order.
-// K is walked in whole rounds of 4*DEPTH blocks: blocks past the end multiply clamped (finite)
+// K is walked in whole rounds of waves*DEPTH blocks: blocks past the end multiply clamped (finite)
 // weight loads with zero-filled input, so the loop has no conditional loads.
 template <typename T, int NT, int DEPTH>
 struct Gemm {
   static constexpr int KB = 256 / (int)sizeof(T);
   static constexpr int EPV = TT<T>::EPV;
-  static constexpr int ROUND = 4 * DEPTH;
+  static constexpr int ROUND = LS_WAVES * DEPTH;
   // a chunk of 16 rows must hold at least one round
   static_assert(LS_ACT_BYTES / (LS_ROWS * 256) >= ROUND, "LDS chunk too small for this prefetch depth");
   uint4 slot[DEPTH][NT][4];
@@ -417,7 +418,7 @@ struct Gemm {
 #pragma unroll
     for (int t = 0; t < NT; ++t) rp[t] = (wt[t] ? wt[t] : wt[0]) + (size_t)r * K;
 #pragma unroll
-    for (int s = 0; s < DEPTH; ++s) load_slot(s, WAVE + 4 * s);
+    for (int s = 0; s < DEPTH; ++s) load_slot(s, WAVE + LS_WAVES * s);
   }
 
   template <int MODE>
@@ -447,7 +448,7 @@ struct Gemm {
       for (int kb0 = wave; kb0 < clen; kb0 += ROUND) {
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
-          const int kbl = kb0 + 4 * s;   // block within the chunk
+          const int kbl = kb0 + LS_WAVES * s;   // block within the chunk
           uint4 b[4];
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
@@ -478,7 +479,7 @@ __device__ __forceinline__ f32x4 tile_sum(const char* act, int t) {
   const f32x4* red = reinterpret_cast<const f32x4*>(act);
   f32x4 s = red[(0 * NT + t) * 64 + LANE];
 #pragma unroll
-  for (int w = 1; w < 4; ++w) {
+  for (int w = 1; w < LS_WAVES; ++w) {
     const f32x4 v = red[(w * NT + t) * 64 + LANE];
     s[0] += v[0]; s[1] += v[1]; s[2] += v[2]; s[3] += v[3];
   }
@@ -489,7 +490,7 @@ __device__ __forceinline__ f32x4 tile_sum(const char* act, int t) {
 template <typename T>
 __device__ __forceinline__ void compute_rinv(const LsKParams& P, const PassCtx& pc, bool from_embed, Misc* ms) {
   const int lane = LANE, wave = WAVE;
-  for (int n = wave; n < pc.m; n += 4) {
+  for (int n = wave; n < pc.m; n += LS_WAVES) {
     float s = 0.f;
     if (from_embed) {
       const T* e = static_cast<const T*>(P.embed) + (size_t)ms->tok[n] * P.dm;
@@ -616,7 +617,8 @@ template <typename T, int HD>
 __device__ __forceinline__ bool stage_attn(const PassCtx pc, int l) {
   LS_CTX;
   constexpr int TP = LS_ATTN_TILE;
-  constexpr int SEG = HD / 4;           // dims per thread in the q.k product
+  constexpr int NSEG = LS_THREADS / TP; // threads per key in the q.k product
+  constexpr int SEG = HD / NSEG;        // dims per thread in the q.k product
   constexpr int DQ = HD / 4;            // threads across one V row (4 dims each)
   constexpr int PARTS = LS_THREADS / DQ;
   constexpr int KPP = TP / PARTS;       // keys per thread in the p.v product
@@ -630,7 +632,7 @@ __device__ __forceinline__ bool stage_attn(const PassCtx pc, int l) {
   float* sc = qs + 16 * HD;                    // [16][TP]
   float* smx = sc + 16 * TP;                   // [16]
   float* ssm = smx + 16;                       // [16]
-  float* red = ssm + 16;                       // [4][16][HD]
+  float* red = ssm + 16;                       // [waves][16][HD]
   const T* kc = static_cast<const T*>(P.kcache) + (size_t)l * P.nkv * P.max_seq * HD;
   const T* vc = static_cast<const T*>(P.vcache) + (size_t)l * P.nkv * P.max_seq * HD;
 
@@ -642,7 +644,7 @@ __device__ __forceinline__ bool stage_attn(const PassCtx pc, int l) {
     const int kp0 = ti * TP;
     const int nvalid = (tend - kp0 < TP) ? tend - kp0 : TP;
     // K: thread (key u, segment seg); V: thread (dim quad dq, key part)
-    const int u = tid >> 2, seg = tid & 3;
+    const int u = tid / NSEG, seg = tid % NSEG;
     float kreg[SEG];
     {
       const bool ok = u < nvalid;   // keys past the end read key 0 of the tile and are zeroed
@@ -683,15 +685,15 @@ __device__ __forceinline__ bool stage_attn(const PassCtx pc, int l) {
           const float4 qv = *reinterpret_cast<const float4*>(q + e);
           dot += kreg[e] * qv.x; dot += kreg[e + 1] * qv.y; dot += kreg[e + 2] * qv.z; dot += kreg[e + 3] * qv.w;
         }
-        dot += __shfl_xor(dot, 1);
-        dot += __shfl_xor(dot, 2);
+#pragma unroll
+        for (int o = 1; o < NSEG; o <<= 1) dot += __shfl_xor(dot, o);
         if (seg == 0) {
           const int qpos = pc.pos0 + (qb + qi) / G;
           sc[qi * TP + u] = (u < nvalid && kp0 + u <= qpos) ? dot * P.attn_scale : -INFINITY;
         }
       }
       lds_barrier();
-      for (int qi = wave; qi < nqb; qi += 4) {
+      for (int qi = wave; qi < nqb; qi += LS_WAVES) {
         const float s = sc[qi * TP + lane];
         float mx = s;
 #pragma unroll
@@ -723,8 +725,12 @@ __device__ __forceinline__ bool stage_attn(const PassCtx pc, int l) {
         float o[2];
 #pragma unroll
         for (int e = 0; e < 2; ++e)
-          o[e] = ((red[(0 * 16 + qi) * HD + dim + e] + red[(1 * 16 + qi) * HD + dim + e]) +
-                  red[(2 * 16 + qi) * HD + dim + e]) + red[(3 * 16 + qi) * HD + dim + e];
+        {
+          float a = red[(0 * 16 + qi) * HD + dim + e];
+#pragma unroll
+          for (int w = 1; w < LS_WAVES; ++w) a += red[(w * 16 + qi) * HD + dim + e];
+          o[e] = a;
+        }
         float* dst = pout + (size_t)(qb + qi) * PSTRIDE;
         stcf2(dst + dim, o[0], o[1]);
         if (dim == 0) stcf2(dst + HD, smx[qi], ssm[qi]);
@@ -746,7 +752,7 @@ __device__ __forceinline__ bool stage_attn(const PassCtx pc, int l) {
       for (int qb = 0; qb < nQ; qb += 16) {
         const int nqb = (nQ - qb < 16) ? nQ - qb : 16;
         lds_barrier();
-        for (int qi = wave; qi < nqb; qi += 4) {
+        for (int qi = wave; qi < nqb; qi += LS_WAVES) {
           const int qg = qb + qi;
           float M = -INFINITY;
           for (int t = lane; t < ntiles; t += 64) M = fmaxf(M, ldcf(pin + ((size_t)t * 64 + qg) * PSTRIDE + HD));
@@ -857,7 +863,7 @@ __device__ __forceinline__ bool stage_resid(const PassCtx pc, int l, bool is_dow
     if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, K); }
     G.template run<ACT_PLAIN>(A, P, ms, pc.m, act);
     LS_PROF(is_down ? 0x54 : 0x34);
-    for (int t = wave; t < NT; t += 4) {
+    for (int t = wave; t < NT; t += LS_WAVES) {
       const int tile = grp * NT + t;
       if (tile >= tiles) continue;
       const f32x4 v = tile_sum<NT>(act, t);
@@ -1014,9 +1020,8 @@ __device__ __noinline__ bool stage_head(const PassCtx pc) {
   lds_barrier();
   if (TID < LS_ROWS) {
     Best b = ms->wb[0][TID];
-    b = best_merge(b, ms->wb[1][TID]);
-    b = best_merge(b, ms->wb[2][TID]);
-    b = best_merge(b, ms->wb[3][TID]);
+#pragma unroll
+    for (int w = 1; w < LS_WAVES; ++w) b = best_merge(b, ms->wb[w][TID]);
     float* dst = P.cand + ((size_t)blockIdx.x * LS_ROWS + TID) * 4;
     stcf2(dst, b.v1, __int_as_float(b.i1));
     stcf2(dst + 2, b.v2, 0.f);
@@ -1049,9 +1054,8 @@ __device__ __noinline__ bool reduce_cands(const PassCtx pc) {
   lds_barrier();
   if (TID < pc.m) {
     Best b = ms->wb[0][TID];
-    b = best_merge(b, ms->wb[1][TID]);
-    b = best_merge(b, ms->wb[2][TID]);
-    b = best_merge(b, ms->wb[3][TID]);
+#pragma unroll
+    for (int w = 1; w < LS_WAVES; ++w) b = best_merge(b, ms->wb[w][TID]);
     ms->r_tok[TID] = b.i1;
     ms->r_margin[TID] = b.v1 - b.v2;
   }
@@ -1255,9 +1259,9 @@ __device__ __forceinline__ void program_body(const LsKParams& Pk) {
 
 // Two kernel symbols so that profiles separate the prompt passes from the decode rounds.
 template <typename T>
-__global__ __launch_bounds__(LS_THREADS, 2) void ls_prompt_kernel(const LsKParams P) { program_body<T>(P); }
+__global__ __launch_bounds__(LS_THREADS, 1) void ls_prompt_kernel(const LsKParams P) { program_body<T>(P); }
 template <typename T>
-__global__ __launch_bounds__(LS_THREADS, 2) void ls_decode_kernel(const LsKParams P) { program_body<T>(P); }
+__global__ __launch_bounds__(LS_THREADS, 1) void ls_decode_kernel(const LsKParams P) { program_body<T>(P); }
 
 // ------------------------------------------------------------------------------------------
 static const void* kernel_for(int kind, int dtype_is_bf16) {

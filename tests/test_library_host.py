@@ -1,0 +1,79 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, sizes workspaces, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import workloads as W
+from paper_2404_16710_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _header_functions():
+    src = open(os.path.join(ROOT, "include", "ls.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(ls_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    names = _header_functions()
+    assert set(names) >= {"ls_load_weights", "ls_prefill", "ls_draft", "ls_verify", "ls_generate"}
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(B.EXPORTS) == set(names)
+
+
+def test_workspace_sizes_follow_the_configuration():
+    lib = B.lib()
+    for name in ("c1", "c2", "c3", "c4", "c5"):
+        w = W.get_workload(name)
+        m = w.model
+        max_seq = w.n_prompt + w.n_new + 17
+        cfg = B.config_struct(m, max_seq)
+        n = lib.ls_workspace_bytes(C.byref(cfg))
+        kv = 2 * m.n_layers * m.kv_dim * max_seq * m.elem_bytes
+        assert kv < n < kv + (64 << 20), (name, n, kv)
+
+
+@pytest.mark.parametrize("field,value", [("head_dim", 96), ("n_kv_heads", 3), ("d_model", 250), ("vocab", 1001),
+                                         ("max_draft", 16), ("max_draft", 0), ("dtype", 7), ("max_seq", 1),
+                                         ("max_seq", 1 << 20), ("n_layers", 0), ("rms_eps", 0.0)])
+def test_invalid_configurations_are_rejected(field, value):
+    lib = B.lib()
+    cfg = B.config_struct(W.get_workload("c1").model, 128)
+    setattr(cfg, field, value)
+    assert lib.ls_workspace_bytes(C.byref(cfg)) == 0
+    ctx = C.c_void_p()
+    w = B.ls_weights()
+    assert lib.ls_load_weights(C.byref(cfg), C.byref(w), C.c_void_p(256), 1 << 30, C.byref(ctx)) == -1
+    assert not ctx.value
+
+
+def test_null_and_misaligned_arguments_are_rejected_without_a_gpu():
+    lib = B.lib()
+    cfg = B.config_struct(W.get_workload("c1").model, 128)
+    ctx = C.c_void_p()
+    w = B.ls_weights()                                      # all pointers null
+    assert lib.ls_load_weights(C.byref(cfg), C.byref(w), C.c_void_p(256), 1 << 30, C.byref(ctx)) == -1
+    assert lib.ls_load_weights(C.byref(cfg), None, C.c_void_p(256), 1 << 30, C.byref(ctx)) == -1
+    assert lib.ls_load_weights(C.byref(cfg), C.byref(w), None, 1 << 30, C.byref(ctx)) == -1
+    assert lib.ls_load_weights(C.byref(cfg), C.byref(w), C.c_void_p(257), 1 << 30, C.byref(ctx)) == -1
+    for fn, args in (("ls_prefill", (None, None, 4, None)), ("ls_draft", (None, 1, 1, None)),
+                     ("ls_verify", (None, 1, 1, None)), ("ls_get_state", (None, None, None, None, None)),
+                     ("ls_debug_capture", (None, None)), ("ls_set_launch", (None, 1))):
+        assert getattr(lib, fn)(*args) == -1, fn
+    assert b"capacity" in lib.ls_strerror(-3) and b"ok" == lib.ls_strerror(0)
+    lib.ls_destroy(None)                                     # harmless
+
+
+def test_binding_refuses_to_run_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    w = W.get_workload("c1")
+    with pytest.raises(RuntimeError):
+        B.LsModel(w.model, W.make_weights(w), max_seq=128)
