@@ -55,6 +55,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-new", type=int, default=24)
     ap.add_argument("--wg-per-cu", type=int, default=0)
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run the library's plain copy kernel over this many MiB (byte-counter reference)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
@@ -80,6 +82,8 @@ def main() -> int:
     print(f"[bench] {m.name}: weights generated in {t_gen:.1f}s, uploaded; E={E} d={d} "
           f"P={w.n_prompt} N={w.n_new}", file=sys.stderr, flush=True)
 
+    if a.calibration_copy_mib:
+        model.debug_copy(a.calibration_copy_mib << 20)
     for _ in range(a.warmup):
         model.generate(prompt, w.n_new, E, d)
     torch.cuda.synchronize()
@@ -127,7 +131,7 @@ def main() -> int:
                         "hbm_gbs": round(ach_ar, 1), "hbm_frac": round(ach_ar / HBM_PEAK_GBS, 4)},
         "speedup_vs_full_greedy": round(ar_ms_dec / ms_dec, 3),
         "same_ids_as_full_greedy": bool(toks == ar_toks),
-        "roofline": {"bound": "hbm", "kernel": "ls_decode_kernel (draft + tail + verify passes of all rounds)",
+        "roofline": {"bound": "hbm", "kernel": "ls_decode_kernel<bf16> (one launch = all draft + tail + verify passes of a job)",
                      "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
                      "bytes_per_launch": int(b_ss), "ms_per_launch": round(ms_dec, 3)},

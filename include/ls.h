@@ -155,6 +155,11 @@ int ls_debug_capture(ls_ctx *ctx, float *dev_hidden);
  * launch); NULL switches it off.  Used to see where a pass spends its time. */
 int ls_debug_timeline(ls_ctx *ctx, unsigned long long *dev_events, int32_t capacity, int32_t workgroup);
 
+/* Measurement aid: copies `bytes` (a multiple of 16; both pointers DEVICE, 16-byte aligned) with
+ * a plain copy kernel (ls_copy_kernel).  Profilers use it as the known-size reference that hardware
+ * byte counters are scaled by.  Enqueue only. */
+int ls_debug_copy(void *dev_dst, const void *dev_src, size_t bytes, void *stream);
+
 /* Launch shape: workgroups per compute unit (1 or 2) used by later calls; 0 restores the default.
  * Returns the number of workgroups a launch will use, or a negative error. */
 int ls_set_launch(ls_ctx *ctx, int32_t workgroups_per_cu);

@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 EXPORTS = (
     "ls_workspace_bytes", "ls_load_weights", "ls_prefill", "ls_draft", "ls_verify", "ls_generate",
     "ls_generate_early_exit", "ls_score", "ls_get_state", "ls_peek_round", "ls_debug_capture",
-    "ls_debug_timeline", "ls_set_launch", "ls_strerror", "ls_destroy",
+    "ls_debug_timeline", "ls_debug_copy", "ls_set_launch", "ls_strerror", "ls_destroy",
 )
 
 
@@ -104,6 +104,8 @@ def lib() -> C.CDLL:
     L.ls_debug_capture.argtypes = [vp, vp]
     L.ls_debug_timeline.restype = C.c_int
     L.ls_debug_timeline.argtypes = [vp, vp, i32, i32]
+    L.ls_debug_copy.restype = C.c_int
+    L.ls_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
     L.ls_set_launch.restype = C.c_int
     L.ls_set_launch.argtypes = [vp, i32]
     L.ls_strerror.restype = C.c_char_p
@@ -266,6 +268,14 @@ class LsModel:
             _check(self.lib.ls_debug_timeline(self.ctx, None, 0, 0), "ls_debug_timeline")
             self._timeline = None
         return self._timeline
+
+    def debug_copy(self, nbytes: int) -> None:
+        """Runs the library's plain copy kernel over nbytes (counter calibration for profilers)."""
+        src = self.torch.zeros(nbytes, dtype=self.torch.uint8, device=self.device)
+        dst = self.torch.empty_like(src)
+        _check(self.lib.ls_debug_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nbytes, self._stream()),
+               "ls_debug_copy")
+        self.torch.cuda.synchronize(self.device)
 
     def debug_capture(self, on: bool = True):
         """Returns the device tensor [n_layers, max_seq, d_model] that later passes fill."""

@@ -15,6 +15,7 @@
 
 extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid, hipStream_t stream);
 extern "C" int ls_kernel_setup(int dtype_is_bf16, int* max_blocks_per_cu);
+extern "C" int ls_launch_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
 
 namespace {
 
@@ -379,6 +380,11 @@ int ls_debug_timeline(ls_ctx* c, unsigned long long* dev_events, int32_t capacit
   if (dev_events != nullptr && (capacity < 1 || workgroup < 0 || workgroup >= c->grid)) return LS_E_RANGE;
   c->prof = dev_events; c->prof_cap = dev_events ? capacity : 0; c->prof_wg = workgroup;
   return LS_OK;
+}
+
+int ls_debug_copy(void* dev_dst, const void* dev_src, size_t bytes, void* stream) {
+  if (!dev_dst || !dev_src || bytes == 0 || bytes % 16 || ((uintptr_t)dev_dst | (uintptr_t)dev_src) % 16) return LS_E_ARG;
+  return ls_launch_copy(dev_src, dev_dst, bytes, static_cast<hipStream_t>(stream)) == 0 ? LS_OK : LS_E_HIP;
 }
 
 const char* ls_strerror(int code) {

@@ -1257,19 +1257,36 @@ __device__ __forceinline__ void program_body(const LsKParams& Pk) {
   }
 }
 
-// Two kernel symbols so that profiles separate the prompt passes from the decode rounds.
+// Three kernel symbols so that profiles separate the prompt passes, the self-speculative rounds
+// and plain full-model greedy decoding.
 template <typename T>
 __global__ __launch_bounds__(LS_THREADS, 1) void ls_prompt_kernel(const LsKParams P) { program_body<T>(P); }
 template <typename T>
 __global__ __launch_bounds__(LS_THREADS, 1) void ls_decode_kernel(const LsKParams P) { program_body<T>(P); }
+template <typename T>
+__global__ __launch_bounds__(LS_THREADS, 1) void ls_greedy_kernel(const LsKParams P) { program_body<T>(P); }
+
+// Plain copy, 16 bytes per thread per step: the known-size reference for hardware byte counters.
+__global__ __launch_bounds__(256) void ls_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+extern "C" int ls_launch_copy(const void* src, void* dst, size_t bytes, hipStream_t stream) {
+  ls_copy_kernel<<<dim3(2048), dim3(256), 0, stream>>>(static_cast<const uint4*>(src), static_cast<uint4*>(dst), bytes / 16);
+  return hipGetLastError() == hipSuccess ? 0 : 1;
+}
 
 // ------------------------------------------------------------------------------------------
-static const void* kernel_for(int kind, int dtype_is_bf16) {
+static const void* kernel_for(int kind, int d, int dtype_is_bf16) {
   const bool prompt = kind == LS_PROG_PREFILL || kind == LS_PROG_SCORE;
+  const bool greedy = kind == LS_PROG_GENERATE && d == 0;
   if (dtype_is_bf16)
     return prompt ? reinterpret_cast<const void*>(&ls_prompt_kernel<bf16_t>)
+         : greedy ? reinterpret_cast<const void*>(&ls_greedy_kernel<bf16_t>)
                   : reinterpret_cast<const void*>(&ls_decode_kernel<bf16_t>);
   return prompt ? reinterpret_cast<const void*>(&ls_prompt_kernel<float>)
+       : greedy ? reinterpret_cast<const void*>(&ls_greedy_kernel<float>)
                 : reinterpret_cast<const void*>(&ls_decode_kernel<float>);
 }
 
@@ -1279,17 +1296,17 @@ extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid
   // so an ordinary launch is used; LS_COOPERATIVE_LAUNCH=1 asks the runtime to guarantee residency.
   static const bool coop = []() { const char* v = getenv("LS_COOPERATIVE_LAUNCH"); return v != nullptr && v[0] == '1'; }();
   const size_t smem = LS_SMEM_BYTES + (p->prof != nullptr ? LS_PROF_EVENTS * 8 : 0);
-  hipError_t e = coop ? hipLaunchCooperativeKernel(kernel_for(p->kind, dtype_is_bf16), dim3(grid), dim3(LS_THREADS),
+  hipError_t e = coop ? hipLaunchCooperativeKernel(kernel_for(p->kind, p->d, dtype_is_bf16), dim3(grid), dim3(LS_THREADS),
                                                    args, smem, stream)
-                      : hipLaunchKernel(kernel_for(p->kind, dtype_is_bf16), dim3(grid), dim3(LS_THREADS), args,
+                      : hipLaunchKernel(kernel_for(p->kind, p->d, dtype_is_bf16), dim3(grid), dim3(LS_THREADS), args,
                                         smem, stream);
   return e == hipSuccess ? 0 : (int)e;
 }
 
 extern "C" int ls_kernel_setup(int dtype_is_bf16, int* max_blocks_per_cu) {
   int nb_min = 1 << 30;
-  for (int kind : {(int)LS_PROG_PREFILL, (int)LS_PROG_GENERATE}) {
-    const void* fn = kernel_for(kind, dtype_is_bf16);
+  for (int v = 0; v < 3; ++v) {
+    const void* fn = kernel_for(v == 0 ? (int)LS_PROG_PREFILL : (int)LS_PROG_GENERATE, v == 1 ? 0 : 1, dtype_is_bf16);
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LS_SMEM_BYTES + LS_PROF_EVENTS * 8);
     if (e != hipSuccess) return (int)e;
     int nb = 0;
