@@ -11,7 +11,8 @@
 #define LS_ATTN_TILE 64         // KV positions per attention work item
 #define LS_ACT_BYTES (64 * 1024) // LDS bytes for staged matmul inputs
 #define LS_MISC_BYTES 6656       // LDS bytes for state, statistics and small scratch
-#define LS_SMEM_BYTES (LS_ACT_BYTES + LS_MISC_BYTES)
+#define LS_RED_BYTES 8192        // LDS bytes for the cross-wave reduction of accumulator tiles
+#define LS_SMEM_BYTES (LS_ACT_BYTES + LS_RED_BYTES + LS_MISC_BYTES)
 
 struct LsLayerW {
   const void *wq, *wk, *wv, *wo, *wg, *wu, *wd, *attn_norm, *ffn_norm;

@@ -160,7 +160,7 @@ struct Misc {
 static_assert(sizeof(Misc) <= LS_MISC_BYTES, "Misc must fit its LDS slot");
 
 extern __shared__ __align__(16) char ls_smem[];
-__device__ __forceinline__ Misc* MS() { return reinterpret_cast<Misc*>(ls_smem + LS_ACT_BYTES); }
+__device__ __forceinline__ Misc* MS() { return reinterpret_cast<Misc*>(ls_smem + LS_ACT_BYTES + LS_RED_BYTES); }
 // Every stage function starts with this: LDS views that the compiler can see are LDS.
 #define LS_CTX                      \
   Misc* const ms = MS();            \
@@ -394,19 +394,26 @@ struct Gemm {
   static constexpr int ROUND = LS_WAVES * DEPTH;
   // a chunk of 16 rows must hold at least one round
   static_assert(LS_ACT_BYTES / (LS_ROWS * 256) >= ROUND, "LDS chunk too small for this prefetch depth");
+  static_assert(LS_WAVES * NT * 64 * 16 <= LS_RED_BYTES, "reduction scratch too small");
   uint4 slot[DEPTH][NT][4];
-  const T* rp[NT];
-  int K, nkb;
+  const T* rp[NT];       // row pointers of the current group of tiles
+  const T* rp_next[NT];  // ... of the group this workgroup multiplies next (or the same again)
+  int K, nkb, nkb_pad;
 
+  // Blocks are numbered along K of the current group and continue into the next group: the loads
+  // that run past the end of this group already fetch the first blocks of the next one.
   __device__ __forceinline__ void load_slot(int s, int kb) {
     const int e0 = (LANE >> 4) * EPV;
+    const bool nxt = kb >= nkb_pad;
+    const int kbb = nxt ? kb - nkb_pad : kb;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
+      const T* base = nxt ? rp_next[t] : rp[t];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int idx = e0 + kb * KB + j * (KB / 4);
+        const int idx = e0 + kbb * KB + j * (KB / 4);
         const int idc = (idx + EPV <= K) ? idx : 0;
-        slot[s][t][j] = ldg128(rp[t] + idc);
+        slot[s][t][j] = ldg128(base + idc);
       }
     }
   }
@@ -415,17 +422,28 @@ struct Gemm {
     const int r = LANE & 15;
     K = K_;
     nkb = (K + KB - 1) / KB;
+    nkb_pad = (nkb + ROUND - 1) / ROUND * ROUND;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) rp[t] = (wt[t] ? wt[t] : wt[0]) + (size_t)r * K;
+    for (int t = 0; t < NT; ++t) rp_next[t] = rp[t] = (wt[t] ? wt[t] : wt[0]) + (size_t)r * K;
 #pragma unroll
     for (int s = 0; s < DEPTH; ++s) load_slot(s, WAVE + LS_WAVES * s);
   }
+  __device__ __forceinline__ void set_next(const T* const (&wt)[NT]) {
+    const int r = LANE & 15;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) rp_next[t] = (wt[t] ? wt[t] : wt[0]) + (size_t)r * K;
+  }
+  __device__ __forceinline__ void advance() {
+#pragma unroll
+    for (int t = 0; t < NT; ++t) rp[t] = rp_next[t];
+  }
 
   template <int MODE>
-  __device__ __forceinline__ void run(const ActDesc& A, const LsKParams& P, Misc* ms, int m, char* act) {
+  // `staged` (in/out): the input of this stage is already in LDS from an earlier group; it stays
+  // valid when all of K fits one chunk.
+  __device__ __forceinline__ void run(const ActDesc& A, const LsKParams& P, Misc* ms, int m, char* act, bool& staged) {
     const int lane = LANE, wave = WAVE;
     const int r = lane & 15, g = lane >> 4;
-    const int nkb_pad = (nkb + ROUND - 1) / ROUND * ROUND;
     int kcb = (LS_ACT_BYTES / (m * 256)) / ROUND * ROUND;
     if (kcb > nkb_pad) kcb = nkb_pad;
     const int rs_units = kcb * 16;
@@ -440,11 +458,13 @@ struct Gemm {
     for (int c0 = 0; c0 < nkb_pad; c0 += kcb) {
       const int clen = (c0 + kcb <= nkb_pad) ? kcb : nkb_pad - c0;
       if (c0) lds_barrier();
-      if (MODE == ACT_NORM_X && c0 == 0 && A.ssq != nullptr)
-        stage_act_norm_first<T>(A, P, ms, m, K, clen * KB, rs_units, act);
-      else
-        stage_act<T, MODE>(A, ms, m, K, c0 * KB, clen * KB, rs_units, act);
-      lds_barrier();
+      if (!staged) {
+        if (MODE == ACT_NORM_X && c0 == 0 && A.ssq != nullptr)
+          stage_act_norm_first<T>(A, P, ms, m, K, clen * KB, rs_units, act);
+        else
+          stage_act<T, MODE>(A, ms, m, K, c0 * KB, clen * KB, rs_units, act);
+        lds_barrier();
+      }
       for (int kb0 = wave; kb0 < clen; kb0 += ROUND) {
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
@@ -466,8 +486,8 @@ struct Gemm {
         }
       }
     }
-    lds_barrier();
-    f32x4* red = reinterpret_cast<f32x4*>(act);
+    staged = (kcb == nkb_pad);
+    f32x4* red = reinterpret_cast<f32x4*>(ls_smem + LS_ACT_BYTES);
 #pragma unroll
     for (int t = 0; t < NT; ++t) red[(wave * NT + t) * 64 + lane] = acc[t];
     lds_barrier();
@@ -476,7 +496,8 @@ struct Gemm {
 
 template <int NT>
 __device__ __forceinline__ f32x4 tile_sum(const char* act, int t) {
-  const f32x4* red = reinterpret_cast<const f32x4*>(act);
+  (void)act;
+  const f32x4* red = reinterpret_cast<const f32x4*>(ls_smem + LS_ACT_BYTES);
   f32x4 s = red[(0 * NT + t) * 64 + LANE];
 #pragma unroll
   for (int w = 1; w < LS_WAVES; ++w) {
@@ -563,11 +584,18 @@ __device__ __forceinline__ bool stage_qkv(const PassCtx pc, int l) {
   LS_PROF(0x12);
   if (emb) compute_rinv<T>(P, pc, true, ms);
   LS_PROF(0x13);
+  bool staged = false;
   for (; grp < groups; grp += gridDim.x) {
-    if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, dm); }
-    if (emb) G.template run<ACT_NORM_EMB>(A, P, ms, pc.m, act);
-    else G.template run<ACT_NORM_X>(A, P, ms, pc.m, act);
+    {
+      const T* wtn[NT];
+      const int nx = grp + (int)gridDim.x;
+      tiles_of(nx < groups ? nx : grp, wtn);
+      G.set_next(wtn);
+    }
+    if (emb) G.template run<ACT_NORM_EMB>(A, P, ms, pc.m, act, staged);
+    else G.template run<ACT_NORM_X>(A, P, ms, pc.m, act, staged);
     LS_PROF(0x14);
+    G.advance();
     if (wave < IPG) {
       const int item = grp * IPG + wave;
       if (item < items) {
@@ -859,10 +887,17 @@ __device__ __forceinline__ bool stage_resid(const PassCtx pc, int l, bool is_dow
   LS_PROF(is_down ? 0x51 : 0x31);
   if (!grid_wait(P, ms)) return false;
   LS_PROF(is_down ? 0x52 : 0x32);
+  bool staged = false;
   for (; grp < groups; grp += gridDim.x) {
-    if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, K); }
-    G.template run<ACT_PLAIN>(A, P, ms, pc.m, act);
+    {
+      const T* wtn[NT];
+      const int nx = grp + (int)gridDim.x;
+      tiles_of(nx < groups ? nx : grp, wtn);
+      G.set_next(wtn);
+    }
+    G.template run<ACT_PLAIN>(A, P, ms, pc.m, act, staged);
     LS_PROF(is_down ? 0x54 : 0x34);
+    G.advance();
     for (int t = wave; t < NT; t += LS_WAVES) {
       const int tile = grp * NT + t;
       if (tile >= tiles) continue;
@@ -937,10 +972,17 @@ __device__ __forceinline__ bool stage_gu(const PassCtx pc, int l) {
   if (!grid_wait(P, ms)) return false;
   LS_PROF(0x42);
   LS_PROF(0x43);
+  bool staged = false;
   for (; grp < groups; grp += gridDim.x) {
-    if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, dm); }
-    G.template run<ACT_NORM_X>(A, P, ms, pc.m, act);
+    {
+      const T* wtn[NT];
+      const int nx = grp + (int)gridDim.x;
+      tiles_of(nx < groups ? nx : grp, wtn);
+      G.set_next(wtn);
+    }
+    G.template run<ACT_NORM_X>(A, P, ms, pc.m, act, staged);
     LS_PROF(0x44);
+    G.advance();
     if (wave < IPG) {
       const int item = grp * IPG + wave;
       if (item < items && n < pc.m) {
@@ -998,10 +1040,17 @@ __device__ __noinline__ bool stage_head(const PassCtx pc) {
   if (!grid_wait(P, ms)) return false;
   LS_PROF(0x62);
   LS_PROF(0x63);
+  bool staged = false;
   for (; grp < groups; grp += gridDim.x) {
-    if (grp != (int)blockIdx.x) { tiles_of(grp, wt); G.begin(wt, dm); }
-    G.template run<ACT_NORM_X>(A, P, ms, pc.m, act);
+    {
+      const T* wtn[NT];
+      const int nx = grp + (int)gridDim.x;
+      tiles_of(nx < groups ? nx : grp, wtn);
+      G.set_next(wtn);
+    }
+    G.template run<ACT_NORM_X>(A, P, ms, pc.m, act, staged);
     LS_PROF(0x64);
+    G.advance();
     const int tile = grp * NT + wave;
     if (wave < NT && tile < tiles) {
       const f32x4 v = tile_sum<NT>(act, wave);
