@@ -102,6 +102,12 @@ void set_decomposition(ls_ctx* c) {
   c->base.nt_o = choose_nt(g.d_model / 16, c->grid, false);
   c->base.nt_gu = choose_nt(g.ffn_dim / 16, c->grid, true);
   c->base.nt_down = c->base.nt_o;
+  // attention work items: (kv head, C consecutive 64-position tiles), C the smallest count for
+  // which a full cache gives at most one item per workgroup
+  const int max_tiles = (g.max_seq + LS_ATTN_TILE - 1) / LS_ATTN_TILE;
+  int C = 1;
+  while (g.n_kv_heads * ((max_tiles + C - 1) / C) > c->grid && C < max_tiles) ++C;
+  c->base.attn_ctiles = C;
 }
 
 int launch(ls_ctx* c, LsKParams& p, hipStream_t s) {

@@ -9,7 +9,7 @@
 #define LS_WAVES (LS_THREADS / 64)
 #define LS_ROWS 16              // rows per pass (MFMA N dimension)
 #define LS_ATTN_TILE 64         // KV positions per attention work item
-#define LS_ACT_BYTES (64 * 1024) // LDS bytes for staged matmul inputs
+#define LS_ACT_BYTES (128 * 1024) // LDS bytes for staged matmul inputs
 #define LS_MISC_BYTES 6656       // LDS bytes for state, statistics and small scratch
 #define LS_RED_BYTES 8192        // LDS bytes for the cross-wave reduction of accumulator tiles
 #define LS_SMEM_BYTES (LS_ACT_BYTES + LS_RED_BYTES + LS_MISC_BYTES)
@@ -60,6 +60,7 @@ struct LsKParams {
   float *attn_part;                 // [nkv][max_tiles][64][hd+2]
   uint32_t *attn_cnt;               // [nkv]
   int32_t max_tiles;
+  int32_t attn_ctiles;              // 64-position tiles per attention work item (from the cache capacity)
   float *cand;                      // [grid][16][4]
   uint32_t *bar;                    // grid barrier counter
   LsState *state;

@@ -639,8 +639,11 @@ __device__ __forceinline__ bool stage_qkv(const PassCtx pc, int l) {
 
 // ------------------------------------------------------------------------------------------
 // Stage B: attention of the m query rows (x G query heads per KV head) over the shared cache.
-// A work item is (kv head, 64-position tile); the last workgroup to finish a kv head merges the
-// per-tile partial softmaxes in tile order.
+// A work item is (kv head, super-tile of C consecutive 64-position tiles); C is fixed by the
+// cache capacity, so the partition depends on absolute positions only.  Inside an item the tiles
+// are walked in order with a running softmax (the next tile's K and V are requested while the
+// current one is processed); the last workgroup to finish a kv head merges the per-item partial
+// results in item order.
 template <typename T, int HD>
 __device__ __forceinline__ bool stage_attn(const PassCtx pc, int l) {
   LS_CTX;
@@ -655,151 +658,192 @@ __device__ __forceinline__ bool stage_attn(const PassCtx pc, int l) {
   const int G = P.G, nQ = pc.m * G;
   const int tend = pc.pos0 + pc.m;  // positions in the cache after this pass
   const int ntiles = (tend + TP - 1) / TP;
-  const int items = P.nkv * ntiles;
-  float* qs = reinterpret_cast<float*>(act);  // [16][HD]
-  float* sc = qs + 16 * HD;                    // [16][TP]
-  float* smx = sc + 16 * TP;                   // [16]
-  float* ssm = smx + 16;                       // [16]
-  float* red = ssm + 16;                       // [waves][16][HD]
+  const int C = P.attn_ctiles;
+  const int nsuper = (ntiles + C - 1) / C;
+  const int items = P.nkv * nsuper;
+  float* qs = reinterpret_cast<float*>(act);   // [64][HD]  queries
+  float* orun = qs + 64 * HD;                   // [64][HD]  running output
+  float* mrun = orun + 64 * HD;                 // [64] running max, [64] running sum
+  float* lrun = mrun + 64;
+  float* sc = lrun + 64;                        // [16][TP]
+  float* smx = sc + 16 * TP;                    // [16]
+  float* ssm = smx + 16;                        // [16]
+  float* red = ssm + 16;                        // [waves][16][HD]
   const T* kc = static_cast<const T*>(P.kcache) + (size_t)l * P.nkv * P.max_seq * HD;
   const T* vc = static_cast<const T*>(P.vcache) + (size_t)l * P.nkv * P.max_seq * HD;
+  const int u = tid / NSEG, seg = tid % NSEG;   // K: thread (key u, segment seg)
+  const int dq = tid % DQ, part = tid / DQ;     // V: thread (dim quad dq, key part)
 
   LS_PROF(0x20);
   if (!grid_barrier(P, ms)) return false;
   LS_PROF(0x22);
   for (int item = blockIdx.x; item < items; item += gridDim.x) {
-    const int c = item / ntiles, ti = item - c * ntiles;
-    const int kp0 = ti * TP;
-    const int nvalid = (tend - kp0 < TP) ? tend - kp0 : TP;
-    // K: thread (key u, segment seg); V: thread (dim quad dq, key part)
-    const int u = tid / NSEG, seg = tid % NSEG;
-    float kreg[SEG];
-    {
-      const bool ok = u < nvalid;   // keys past the end read key 0 of the tile and are zeroed
-      const T* kp = kc + ((size_t)c * P.max_seq + kp0 + (ok ? u : 0)) * HD + seg * SEG;
+    const int c = item / nsuper, si = item - c * nsuper;
+    const int t0 = si * C;
+    const int t1 = (t0 + C < ntiles) ? t0 + C : ntiles;
+    float kreg[SEG], vreg[KPP][4], knext[SEG], vnext[KPP][4];
+    auto load_tile = [&](int ti, float (&kr)[SEG], float (&vr)[KPP][4]) {
+      const int kp0 = ti * TP;
+      const int nvalid = (tend - kp0 < TP) ? tend - kp0 : TP;
+      {
+        const bool ok = u < nvalid;   // keys past the end read key 0 of the tile and are zeroed
+        const T* kp = kc + ((size_t)c * P.max_seq + kp0 + (ok ? u : 0)) * HD + seg * SEG;
 #pragma unroll
-      for (int e = 0; e < SEG; e += 4) TT<T>::ldc4(kp + e, &kreg[e]);
+        for (int e = 0; e < SEG; e += 4) TT<T>::ldc4(kp + e, &kr[e]);
 #pragma unroll
-      for (int e = 0; e < SEG; ++e) kreg[e] = ok ? kreg[e] : 0.f;
+        for (int e = 0; e < SEG; ++e) kr[e] = ok ? kr[e] : 0.f;
+      }
+#pragma unroll
+      for (int kk = 0; kk < KPP; ++kk) {
+        const int key = part * KPP + kk;
+        const bool ok = key < nvalid;
+        TT<T>::ldc4(vc + ((size_t)c * P.max_seq + kp0 + (ok ? key : 0)) * HD + dq * 4, vr[kk]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) vr[kk][e] = ok ? vr[kk][e] : 0.f;
+      }
+    };
+    load_tile(t0, kreg, vreg);
+    lds_barrier();   // previous item (or stage) is done with the LDS region
+    for (int idx = tid; idx < nQ * (HD / 4); idx += LS_THREADS) {
+      const int qg = idx / (HD / 4), d4 = (idx - qg * (HD / 4)) * 4;
+      const int n = qg / G, gq = qg - n * G;
+      float f[4];
+      TT<T>::ldc4(static_cast<const T*>(P.qbuf) + (size_t)n * P.qd + (c * G + gq) * HD + d4, f);
+      *reinterpret_cast<float4*>(qs + qg * HD + d4) = make_float4(f[0], f[1], f[2], f[3]);
+      *reinterpret_cast<float4*>(orun + qg * HD + d4) = make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    const int dq = tid % DQ, part = tid / DQ;
-    float vreg[KPP][4];
-#pragma unroll
-    for (int kk = 0; kk < KPP; ++kk) {
-      const int key = part * KPP + kk;
-      const bool ok = key < nvalid;
-      TT<T>::ldc4(vc + ((size_t)c * P.max_seq + kp0 + (ok ? key : 0)) * HD + dq * 4, vreg[kk]);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) vreg[kk][e] = ok ? vreg[kk][e] : 0.f;
-    }
-    float* pout = P.attn_part + ((size_t)(c * P.max_tiles + ti) * 64) * PSTRIDE;
+    if (tid < nQ) { mrun[tid] = -INFINITY; lrun[tid] = 0.f; }
 
-    for (int qb = 0; qb < nQ; qb += 16) {
-      const int nqb = (nQ - qb < 16) ? nQ - qb : 16;
-      lds_barrier();
-      for (int idx = tid; idx < nqb * (HD / 4); idx += LS_THREADS) {
-        const int qi = idx / (HD / 4), d4 = (idx - qi * (HD / 4)) * 4;
-        const int qg = qb + qi, n = qg / G, gq = qg - n * G;
-        float f[4];
-        TT<T>::ldc4(static_cast<const T*>(P.qbuf) + (size_t)n * P.qd + (c * G + gq) * HD + d4, f);
-        *reinterpret_cast<float4*>(qs + qi * HD + d4) = make_float4(f[0], f[1], f[2], f[3]);
+    for (int ti = t0; ti < t1; ++ti) {
+      const int kp0 = ti * TP;
+      const int nvalid = (tend - kp0 < TP) ? tend - kp0 : TP;
+      if (ti + 1 < t1) load_tile(ti + 1, knext, vnext);
+      for (int qb = 0; qb < nQ; qb += 16) {
+        const int nqb = (nQ - qb < 16) ? nQ - qb : 16;
+        lds_barrier();
+        for (int qi = 0; qi < nqb; ++qi) {
+          const float* q = qs + (qb + qi) * HD + seg * SEG;
+          float dot = 0.f;
+#pragma unroll
+          for (int e = 0; e < SEG; e += 4) {
+            const float4 qv = *reinterpret_cast<const float4*>(q + e);
+            dot += kreg[e] * qv.x; dot += kreg[e + 1] * qv.y; dot += kreg[e + 2] * qv.z; dot += kreg[e + 3] * qv.w;
+          }
+#pragma unroll
+          for (int o = 1; o < NSEG; o <<= 1) dot += __shfl_xor(dot, o);
+          if (seg == 0) {
+            const int qpos = pc.pos0 + (qb + qi) / G;
+            sc[qi * TP + u] = (u < nvalid && kp0 + u <= qpos) ? dot * P.attn_scale : -INFINITY;
+          }
+        }
+        lds_barrier();
+        for (int qi = wave; qi < nqb; qi += LS_WAVES) {
+          const float s = sc[qi * TP + lane];
+          float mx = s;
+#pragma unroll
+          for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+          const float p = (s == -INFINITY) ? 0.f : expf(s - mx);
+          float sum = p;
+#pragma unroll
+          for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+          sc[qi * TP + lane] = p;
+          if (lane == 0) { smx[qi] = mx; ssm[qi] = sum; }
+        }
+        lds_barrier();
+        for (int qi = 0; qi < nqb; ++qi) {
+          float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
+#pragma unroll
+          for (int kk = 0; kk < KPP; ++kk) {
+            const float p = sc[qi * TP + part * KPP + kk];
+            o0 += p * vreg[kk][0]; o1 += p * vreg[kk][1]; o2 += p * vreg[kk][2]; o3 += p * vreg[kk][3];
+          }
+#pragma unroll
+          for (int o = DQ; o < 64; o <<= 1) {
+            o0 += __shfl_xor(o0, o); o1 += __shfl_xor(o1, o); o2 += __shfl_xor(o2, o); o3 += __shfl_xor(o3, o);
+          }
+          if (lane < DQ) *reinterpret_cast<float4*>(red + (wave * 16 + qi) * HD + lane * 4) = make_float4(o0, o1, o2, o3);
+        }
+        lds_barrier();
+        // fold this tile into the running softmax of each query (skipped when the tile is fully masked)
+        for (int idx = tid; idx < nqb * (HD / 2); idx += LS_THREADS) {
+          const int qi = idx / (HD / 2), dim = (idx - qi * (HD / 2)) * 2;
+          const float mx = smx[qi], mo = mrun[qb + qi];
+          if (mx != -INFINITY) {
+            const float mn = fmaxf(mo, mx);
+            const float a = (mo == -INFINITY) ? 0.f : expf(mo - mn), b = expf(mx - mn);
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+              float t = red[(0 * 16 + qi) * HD + dim + e];
+#pragma unroll
+              for (int w = 1; w < LS_WAVES; ++w) t += red[(w * 16 + qi) * HD + dim + e];
+              orun[(qb + qi) * HD + dim + e] = orun[(qb + qi) * HD + dim + e] * a + t * b;
+            }
+          }
+        }
+        lds_barrier();
+        if (tid < nqb) {
+          const float mx = smx[tid], mo = mrun[qb + tid];
+          if (mx != -INFINITY) {
+            const float mn = fmaxf(mo, mx);
+            const float a = (mo == -INFINITY) ? 0.f : expf(mo - mn), b = expf(mx - mn);
+            lrun[qb + tid] = lrun[qb + tid] * a + ssm[tid] * b;
+            mrun[qb + tid] = mn;
+          }
+        }
       }
-      lds_barrier();
-      for (int qi = 0; qi < nqb; ++qi) {
-        const float* q = qs + qi * HD + seg * SEG;
-        float dot = 0.f;
+      if (ti + 1 < t1) {
 #pragma unroll
-        for (int e = 0; e < SEG; e += 4) {
-          const float4 qv = *reinterpret_cast<const float4*>(q + e);
-          dot += kreg[e] * qv.x; dot += kreg[e + 1] * qv.y; dot += kreg[e + 2] * qv.z; dot += kreg[e + 3] * qv.w;
-        }
+        for (int e = 0; e < SEG; ++e) kreg[e] = knext[e];
 #pragma unroll
-        for (int o = 1; o < NSEG; o <<= 1) dot += __shfl_xor(dot, o);
-        if (seg == 0) {
-          const int qpos = pc.pos0 + (qb + qi) / G;
-          sc[qi * TP + u] = (u < nvalid && kp0 + u <= qpos) ? dot * P.attn_scale : -INFINITY;
-        }
-      }
-      lds_barrier();
-      for (int qi = wave; qi < nqb; qi += LS_WAVES) {
-        const float s = sc[qi * TP + lane];
-        float mx = s;
+        for (int kk = 0; kk < KPP; ++kk)
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-        const float p = (s == -INFINITY) ? 0.f : expf(s - mx);
-        float sum = p;
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-        sc[qi * TP + lane] = p;
-        if (lane == 0) { smx[qi] = mx; ssm[qi] = sum; }
-      }
-      lds_barrier();
-      for (int qi = 0; qi < nqb; ++qi) {
-        float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < KPP; ++kk) {
-          const float p = sc[qi * TP + part * KPP + kk];
-          o0 += p * vreg[kk][0]; o1 += p * vreg[kk][1]; o2 += p * vreg[kk][2]; o3 += p * vreg[kk][3];
-        }
-#pragma unroll
-        for (int o = DQ; o < 64; o <<= 1) {
-          o0 += __shfl_xor(o0, o); o1 += __shfl_xor(o1, o); o2 += __shfl_xor(o2, o); o3 += __shfl_xor(o3, o);
-        }
-        if (lane < DQ) *reinterpret_cast<float4*>(red + (wave * 16 + qi) * HD + lane * 4) = make_float4(o0, o1, o2, o3);
-      }
-      lds_barrier();
-      for (int idx = tid; idx < nqb * (HD / 2); idx += LS_THREADS) {
-        const int qi = idx / (HD / 2), dim = (idx - qi * (HD / 2)) * 2;
-        float o[2];
-#pragma unroll
-        for (int e = 0; e < 2; ++e)
-        {
-          float a = red[(0 * 16 + qi) * HD + dim + e];
-#pragma unroll
-          for (int w = 1; w < LS_WAVES; ++w) a += red[(w * 16 + qi) * HD + dim + e];
-          o[e] = a;
-        }
-        float* dst = pout + (size_t)(qb + qi) * PSTRIDE;
-        stcf2(dst + dim, o[0], o[1]);
-        if (dim == 0) stcf2(dst + HD, smx[qi], ssm[qi]);
+          for (int e = 0; e < 4; ++e) vreg[kk][e] = vnext[kk][e];
       }
     }
-    // last arriver of this kv head merges the tiles (partials are coherent stores: once they have
-    // completed, whoever sees the counter reach ntiles sees them)
+    lds_barrier();
+    float* pout = P.attn_part + ((size_t)(c * P.max_tiles + si) * 64) * PSTRIDE;
+    for (int idx = tid; idx < nQ * (HD / 2); idx += LS_THREADS) {
+      const int qg = idx / (HD / 2), dim = (idx - qg * (HD / 2)) * 2;
+      float* dst = pout + (size_t)qg * PSTRIDE;
+      stcf2(dst + dim, orun[qg * HD + dim], orun[qg * HD + dim + 1]);
+      if (dim == 0) stcf2(dst + HD, mrun[qg], lrun[qg]);
+    }
+    // last arriver of this kv head merges the items (partials are coherent stores: once they have
+    // completed, whoever sees the counter reach nsuper sees them)
     drain_vmem();
     lds_barrier();
     if (tid == 0) {
       const unsigned old = __hip_atomic_fetch_add((LS_GLOBAL uint32_t*)(P.attn_cnt + c), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      ms->flag = (old == (unsigned)(ntiles - 1));
+      ms->flag = (old == (unsigned)(nsuper - 1));
     }
     lds_barrier();
     if (ms->flag) {
       const float* pin = P.attn_part + ((size_t)(c * P.max_tiles) * 64) * PSTRIDE;
-      float* wts = reinterpret_cast<float*>(act);   // [16][ntiles] softmax weights of the tiles
-      float* dens = wts + 16 * ntiles;              // [16]
+      float* wts = reinterpret_cast<float*>(act);   // [16][nsuper] softmax weights of the items
+      float* dens = wts + 16 * nsuper;              // [16]
       for (int qb = 0; qb < nQ; qb += 16) {
         const int nqb = (nQ - qb < 16) ? nQ - qb : 16;
         lds_barrier();
         for (int qi = wave; qi < nqb; qi += LS_WAVES) {
           const int qg = qb + qi;
           float M = -INFINITY;
-          for (int t = lane; t < ntiles; t += 64) M = fmaxf(M, ldcf(pin + ((size_t)t * 64 + qg) * PSTRIDE + HD));
+          for (int t = lane; t < nsuper; t += 64) M = fmaxf(M, ldcf(pin + ((size_t)t * 64 + qg) * PSTRIDE + HD));
 #pragma unroll
           for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
           float den = 0.f;
-          for (int t0 = 0; t0 < ntiles; t0 += 64) {
-            const int t = t0 + lane;
-            float w = 0.f, l = 0.f;
-            if (t < ntiles) {
+          for (int tb = 0; tb < nsuper; tb += 64) {
+            const int t = tb + lane;
+            float w = 0.f, lsum = 0.f;
+            if (t < nsuper) {
               const float2 stt = ldcf2(pin + ((size_t)t * 64 + qg) * PSTRIDE + HD);
               w = (stt.x == -INFINITY) ? 0.f : expf(stt.x - M);
-              l = stt.y;
-              wts[qi * ntiles + t] = w;
+              lsum = stt.y;
+              wts[qi * nsuper + t] = w;
             }
-            float part = w * l;
+            float part_sum = w * lsum;
 #pragma unroll
-            for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
-            den += part;
+            for (int o = 32; o > 0; o >>= 1) part_sum += __shfl_xor(part_sum, o);
+            den += part_sum;
           }
           if (lane == 0) dens[qi] = den;
         }
@@ -808,14 +852,14 @@ __device__ __forceinline__ bool stage_attn(const PassCtx pc, int l) {
           const int qi = idx / (HD / 2), dim = (idx - qi * (HD / 2)) * 2;
           const int qg = qb + qi;
           float n0 = 0.f, n1 = 0.f;
-          for (int t0 = 0; t0 < ntiles; t0 += 8) {
+          for (int tb = 0; tb < nsuper; tb += 8) {
             float2 ov[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j)
-              ov[j] = ldcf2(pin + ((size_t)((t0 + j < ntiles) ? t0 + j : 0) * 64 + qg) * PSTRIDE + dim);
+              ov[j] = ldcf2(pin + ((size_t)((tb + j < nsuper) ? tb + j : 0) * 64 + qg) * PSTRIDE + dim);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-              const float w = (t0 + j < ntiles) ? wts[qi * ntiles + t0 + j] : 0.f;
+              const float w = (tb + j < nsuper) ? wts[qi * nsuper + tb + j] : 0.f;
               n0 += w * ov[j].x;
               n1 += w * ov[j].y;
             }

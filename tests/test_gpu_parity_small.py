@@ -123,6 +123,26 @@ def test_rounds_replayed_from_oracle_state(name, E, d):
     gm.close()
 
 
+@pytest.mark.parametrize("max_seq", [4096 + 512, 20000])
+def test_large_cache_capacity_groups_attention_tiles(max_seq):
+    """With a large KV capacity one attention work item walks several 64-position tiles with a
+    running softmax; the result must not change."""
+    w = CASES["c1"].with_(n_prompt=150, n_new=40)
+    ws, prompt, om, gm = _setup(w, max_seq=max_seq)
+    ref = O.greedy_full(om, prompt, w.n_new, want_hidden=True)
+    toks, st = gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
+    ar, _ = gm.generate(prompt, w.n_new, 0, 0)
+    same_until_near_tie(toks, ref.tokens, ref.margins)
+    assert toks == ar
+    cap = gm.debug_capture(True)
+    seq = list(prompt) + ref.tokens[:-1]
+    gm.score(seq)
+    hid = cap.cpu().numpy()[:, :len(seq), :]
+    for l in range(w.model.n_layers):
+        assert rel_err_rows(hid[l], ref.hidden[l + 1]) < 1e-4, l
+    gm.close()
+
+
 def test_exit_at_last_layer_accepts_everything_on_gpu():
     w = CASES["c1"]
     ws, prompt, om, gm = _setup(w)
