@@ -16,15 +16,21 @@
 extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid, hipStream_t stream);
 extern "C" int ls_kernel_setup(int dtype_is_bf16, int* max_blocks_per_cu);
 extern "C" int ls_launch_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
+extern "C" int ls_prefill_layers(const LsPfParams* p, const LsLayerW* host_layers, int pos0, int M, hipStream_t s,
+                                 int (*attn)(void*, int, int, int, hipStream_t), void* attn_ctx);
+extern "C" int ls_prefill_finish(const LsPfParams* p, int last_row, hipStream_t s);
 
 namespace {
 
 struct Layout {
   size_t layers, rope_cos, rope_sin, kcache, vcache, xbuf, ssq, qbuf, obuf, actbuf, attn_part, attn_cnt, cand, bar,
-      state, total;
+      state, x_pf, a_pf, q_pf, o_pf, act_pf, total;
+  int pf_rows;
 };
 
 constexpr int kMaxGrid = 1024;
+constexpr int kPrefillRows = 2048;   // prompt rows the GEMM prefill handles per chunk
+constexpr int kPrefillMinRows = 32;  // shorter prompts take the 16-row passes of the decode kernel
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -65,6 +71,12 @@ Layout make_layout(const ls_config* c) {
   L.cand = take(sizeof(float) * 4 * LS_ROWS * kMaxGrid);
   L.bar = take(4096);
   L.state = take(sizeof(LsState));
+  L.pf_rows = c->max_seq < kPrefillRows ? c->max_seq : kPrefillRows;
+  L.x_pf = take(sizeof(float) * L.pf_rows * c->d_model);
+  L.a_pf = take(esz * L.pf_rows * c->d_model);
+  L.q_pf = take(esz * L.pf_rows * qd);
+  L.o_pf = take(esz * L.pf_rows * qd);
+  L.act_pf = take(esz * L.pf_rows * c->ffn_dim);
   L.total = off;
   return L;
 }
@@ -84,6 +96,9 @@ struct ls_ctx {
   float* capture;
   unsigned long long* prof;
   int prof_cap, prof_wg;
+  std::vector<LsLayerW> host_layers;
+  LsPfParams pf;
+  bool gemm_prefill;
 };
 
 namespace {
@@ -202,7 +217,7 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   bool okc = hipMemcpy(c->ws + lay.layers, lw.data(), sizeof(LsLayerW) * lw.size(), hipMemcpyHostToDevice) == hipSuccess;
   okc = okc && hipMemcpy(c->ws + lay.rope_cos, cs.data(), sizeof(float) * cs.size(), hipMemcpyHostToDevice) == hipSuccess;
   okc = okc && hipMemcpy(c->ws + lay.rope_sin, sn.data(), sizeof(float) * sn.size(), hipMemcpyHostToDevice) == hipSuccess;
-  okc = okc && hipMemset(c->ws + lay.xbuf, 0, lay.total - lay.xbuf) == hipSuccess;
+  okc = okc && hipMemset(c->ws + lay.xbuf, 0, lay.x_pf - lay.xbuf) == hipSuccess;
   okc = okc && hipDeviceSynchronize() == hipSuccess;
   for (int i = 0; i < 3 && okc; ++i) okc = hipEventCreate(&c->ev[i]) == hipSuccess;
   if (!okc) { delete c; return LS_E_HIP; }
@@ -230,7 +245,18 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   p.state = reinterpret_cast<LsState*>(c->ws + lay.state);
   p.spin_limit = 1 << 22;
   if (const char* e = getenv("LS_SPIN_LIMIT")) { const int v = atoi(e); if (v > 0) p.spin_limit = v; }
+  p.q_pf = c->ws + lay.q_pf; p.o_pf = c->ws + lay.o_pf;
   set_decomposition(c);
+  c->host_layers = lw;
+  LsPfParams& f = c->pf;
+  memset(&f, 0, sizeof(f));
+  f.is_bf16 = cfg->dtype == LS_BF16; f.dm = p.dm; f.qd = p.qd; f.kvd = p.kvd; f.ffn = p.ffn; f.vocab = p.vocab;
+  f.hd = p.hd; f.nkv = p.nkv; f.max_seq = p.max_seq; f.layers_used = p.L; f.eps = p.eps;
+  f.embed = w->embed; f.rope_cos = p.rope_cos; f.rope_sin = p.rope_sin; f.kcache = p.kcache; f.vcache = p.vcache;
+  f.x_pf = reinterpret_cast<float*>(c->ws + lay.x_pf); f.a_pf = c->ws + lay.a_pf; f.q_pf = c->ws + lay.q_pf;
+  f.o_pf = c->ws + lay.o_pf; f.act_pf = c->ws + lay.act_pf; f.xbuf = p.xbuf; f.ssq = p.ssq;
+  c->gemm_prefill = true;
+  if (const char* e = getenv("LS_PREFILL")) c->gemm_prefill = !(e[0] == 'r' || e[0] == '0');   // "rows": 16-row passes
   *out = c;
   return LS_OK;
 }
@@ -245,13 +271,43 @@ int ls_set_launch(ls_ctx* c, int32_t wg_per_cu) {
   return c->grid;
 }
 
+static int pf_attn_cb(void* vctx, int layer, int pos0, int M, hipStream_t s) {
+  ls_ctx* c = static_cast<ls_ctx*>(vctx);
+  LsKParams p = program(c, LS_PROG_PF_ATTN);
+  p.n_tokens = M; p.pf_layer = layer; p.pf_pos0 = pos0;
+  return launch(c, p, s) == LS_OK ? 0 : 1;
+}
+
+// The prompt pass: GEMM path for prompts of kPrefillMinRows rows or more (in chunks of pf_rows),
+// else the 16-row passes of the decode kernel.  Ends with the decoding state of a finished prefill.
+static int enqueue_prefill(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, int32_t layers_used,
+                           int32_t* dev_out, int32_t eos, int32_t max_new, hipStream_t s) {
+  if (!c->gemm_prefill || n_prompt < kPrefillMinRows) {
+    LsKParams p = program(c, LS_PROG_PREFILL);
+    p.tokens = dev_prompt; p.n_tokens = n_prompt; p.out_tokens = dev_out; p.eos = eos; p.max_new = max_new;
+    p.layers_used = layers_used;
+    return launch(c, p, s);
+  }
+  LsPfParams f = c->pf;
+  f.tokens = dev_prompt; f.layers_used = layers_used; f.capture = c->capture;
+  int last_rows = 0;
+  for (int pos0 = 0; pos0 < n_prompt; pos0 += c->lay.pf_rows) {
+    const int M = n_prompt - pos0 < c->lay.pf_rows ? n_prompt - pos0 : c->lay.pf_rows;
+    if (ls_prefill_layers(&f, c->host_layers.data(), pos0, M, s, pf_attn_cb, c) != 0) return LS_E_HIP;
+    last_rows = M;
+  }
+  if (ls_prefill_finish(&f, last_rows - 1, s) != 0) return LS_E_HIP;
+  LsKParams p = program(c, LS_PROG_PF_FINISH);
+  p.n_tokens = n_prompt; p.out_tokens = dev_out; p.eos = eos; p.max_new = max_new;
+  return launch(c, p, s);
+}
+
 int ls_prefill(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, void* stream) {
   if (!c || !dev_prompt) return LS_E_ARG;
   if (n_prompt < 1) return LS_E_RANGE;
   if (n_prompt + 1 > c->cfg.max_seq) return LS_E_CAPACITY;
-  LsKParams p = program(c, LS_PROG_PREFILL);
-  p.tokens = dev_prompt; p.n_tokens = n_prompt;
-  const int rc = launch(c, p, static_cast<hipStream_t>(stream));
+  const int rc = enqueue_prefill(c, dev_prompt, n_prompt, c->cfg.n_layers, nullptr, -1, 0x7fffffff,
+                                 static_cast<hipStream_t>(stream));
   if (rc != LS_OK) return rc;
   c->prefilled = true; c->drafted = false; c->pos_bound = n_prompt;
   return LS_OK;
@@ -294,10 +350,7 @@ static int generate_impl(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt,
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (hipMemsetAsync(dev_out, 0xFF, sizeof(int32_t) * max_new, s) != hipSuccess) return LS_E_HIP;
   if (hipEventRecord(c->ev[0], s) != hipSuccess) return LS_E_HIP;
-  LsKParams p = program(c, LS_PROG_PREFILL);
-  p.tokens = dev_prompt; p.n_tokens = n_prompt; p.out_tokens = dev_out; p.eos = eos; p.max_new = max_new;
-  p.layers_used = layers_used;
-  int rc = launch(c, p, s);
+  int rc = enqueue_prefill(c, dev_prompt, n_prompt, layers_used, dev_out, eos, max_new, s);
   if (rc != LS_OK) return rc;
   if (hipEventRecord(c->ev[1], s) != hipSuccess) return LS_E_HIP;
   LsKParams g = program(c, LS_PROG_GENERATE);

@@ -42,7 +42,9 @@ enum LsProgramKind {
   LS_PROG_SCORE = 1,     // same, head on every row, argmax/margin written per row
   LS_PROG_DRAFT = 2,
   LS_PROG_VERIFY = 3,
-  LS_PROG_GENERATE = 4   // rounds of draft+verify (d > 0) or single-token passes (d == 0)
+  LS_PROG_GENERATE = 4,  // rounds of draft+verify (d > 0) or single-token passes (d == 0)
+  LS_PROG_PF_ATTN = 5,   // GEMM prefill: attention of rows [pf_pos0, pf_pos0+n_tokens) of layer pf_layer
+  LS_PROG_PF_FINISH = 6  // GEMM prefill: head on residual row 0, then the state of a finished prefill
 };
 
 struct LsKParams {
@@ -73,9 +75,26 @@ struct LsKParams {
   int32_t *out_tokens;
   float *out_margin;
   int32_t spin_limit;
+  // GEMM prefill: q rows / attention output rows of the prompt chunk, and which layer / rows
+  void *q_pf, *o_pf;
+  int32_t pf_layer, pf_pos0;
   // optional timeline of one workgroup: (100 MHz wall clock << 8) | tag, appended per event
   unsigned long long *prof;
   int32_t prof_cap, prof_wg;
+};
+
+// Parameters of the GEMM prefill (host side launches; see ls_prefill.hip).
+struct LsPfParams {
+  int32_t is_bf16, dm, qd, kvd, ffn, vocab, hd, nkv, max_seq, layers_used;
+  float eps;
+  const int32_t *tokens;
+  const void *embed;
+  const float *rope_cos, *rope_sin;
+  void *kcache, *vcache;
+  float *x_pf;                 // [pf_rows][dm] residual rows of the chunk
+  void *a_pf, *q_pf, *o_pf, *act_pf;  // [pf_rows][dm], [..][qd], [..][qd], [..][ffn] in the model dtype
+  float *xbuf, *ssq;           // decode residual row 0 and its statistics (target of the finish step)
+  float *capture;
 };
 
 #endif

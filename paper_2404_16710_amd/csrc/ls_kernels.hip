@@ -194,6 +194,8 @@ struct PassCtx {
   int m, row0, pos0, l0, l1;
   bool embed_src;  // rows come from the embedding table (tokens in Misc::tok) instead of xbuf
   bool head;
+  void* qrows;     // q rows of the pass [m][qd] (written by the QKV stage, read by attention)
+  void* orows;     // attention output rows [m][qd]
 };
 
 __device__ __forceinline__ Best best_merge(const Best& a, const Best& b) {
@@ -606,7 +608,7 @@ __device__ __forceinline__ bool stage_qkv(const PassCtx pc, int l) {
             const bool isq = item < nq_items;
             const int it = isq ? item : item - nq_items;
             const int h = it / pph, jb = it - h * pph;
-            T* dst = isq ? static_cast<T*>(P.qbuf) + (size_t)n * P.qd + h * hd
+            T* dst = isq ? static_cast<T*>(pc.qrows) + (size_t)n * P.qd + h * hd
                          : static_cast<T*>(P.kcache) + (((size_t)l * P.nkv + h) * P.max_seq + pos) * hd;
             float lo[4], hi[4];
 #pragma unroll
@@ -708,7 +710,7 @@ __device__ __forceinline__ bool stage_attn(const PassCtx pc, int l) {
       const int qg = idx / (HD / 4), d4 = (idx - qg * (HD / 4)) * 4;
       const int n = qg / G, gq = qg - n * G;
       float f[4];
-      TT<T>::ldc4(static_cast<const T*>(P.qbuf) + (size_t)n * P.qd + (c * G + gq) * HD + d4, f);
+      TT<T>::ldc4(static_cast<const T*>(pc.qrows) + (size_t)n * P.qd + (c * G + gq) * HD + d4, f);
       *reinterpret_cast<float4*>(qs + qg * HD + d4) = make_float4(f[0], f[1], f[2], f[3]);
       *reinterpret_cast<float4*>(orun + qg * HD + d4) = make_float4(0.f, 0.f, 0.f, 0.f);
     }
@@ -866,7 +868,7 @@ __device__ __forceinline__ bool stage_attn(const PassCtx pc, int l) {
           }
           const float den = dens[qi];
           const int n = qg / G, gq = qg - n * G;
-          TT<T>::stc2(static_cast<T*>(P.obuf) + (size_t)n * P.qd + (c * G + gq) * HD + dim, n0 / den, n1 / den);
+          TT<T>::stc2(static_cast<T*>(pc.orows) + (size_t)n * P.qd + (c * G + gq) * HD + dim, n0 / den, n1 / den);
         }
       }
       if (tid == 0) stc32(P.attn_cnt + c, 0u);
@@ -893,7 +895,7 @@ __device__ __forceinline__ bool stage_resid(const PassCtx pc, int l, bool is_dow
   const int groups = (tiles + NT - 1) / NT;
   ActDesc A;
   A.mode = ACT_PLAIN;
-  A.src = is_down ? P.actbuf : P.obuf;
+  A.src = is_down ? P.actbuf : pc.orows;
   A.ld = K;
   A.gain = nullptr;
   A.ssq = nullptr;
@@ -1200,6 +1202,7 @@ template <typename T>
 __device__ __forceinline__ bool do_draft(int E, int d) {
   LS_CTX;
   PassCtx pc;
+  pc.qrows = P.qbuf; pc.orows = P.obuf;
   pc.m = 1; pc.l0 = 0; pc.l1 = E; pc.embed_src = true;
   for (int i = 0; i <= d; ++i) {
     if (TID == 0) ms->tok[0] = clamp_tok(i == 0 ? ms->st.last : ms->st.D[i - 1], P.vocab);
@@ -1219,6 +1222,7 @@ template <typename T>
 __device__ __forceinline__ bool do_verify(int E, int d) {
   LS_CTX;
   PassCtx pc;
+  pc.qrows = P.qbuf; pc.orows = P.obuf;
   pc.m = d + 1; pc.row0 = 0; pc.pos0 = ms->st.pos; pc.l0 = E; pc.l1 = P.L; pc.embed_src = false; pc.head = true;
   if (!run_pass<T>(pc)) return false;
   if (TID == 0) {
@@ -1274,6 +1278,7 @@ __device__ __forceinline__ void program_body(const LsKParams& Pk) {
     const int n = P.n_tokens;
     for (int c0 = 0; c0 < n && ok; c0 += LS_ROWS) {
       PassCtx pc;
+  pc.qrows = P.qbuf; pc.orows = P.obuf;
       pc.m = (n - c0 < LS_ROWS) ? n - c0 : LS_ROWS;
       pc.row0 = 0; pc.pos0 = c0; pc.l0 = 0; pc.l1 = P.layers_used; pc.embed_src = true;
       pc.head = (P.kind == LS_PROG_SCORE) || (c0 + LS_ROWS >= n);
@@ -1299,6 +1304,35 @@ __device__ __forceinline__ void program_body(const LsKParams& Pk) {
       }
       __syncthreads();
     }
+  } else if (P.kind == LS_PROG_PF_ATTN) {
+    // attention of prompt rows in blocks of 64/G query rows over the cache (K, V of all rows are in)
+    const int n = P.n_tokens;
+    const int rows = 64 / P.G;   // the attention stage takes up to 64 (row, query head) pairs per kv head
+    for (int c0 = 0; c0 < n && ok; c0 += rows) {
+      PassCtx pc;
+      pc.m = (n - c0 < rows) ? n - c0 : rows;
+      pc.row0 = 0; pc.pos0 = P.pf_pos0 + c0; pc.l0 = pc.l1 = P.pf_layer; pc.embed_src = false; pc.head = false;
+      const size_t esz = sizeof(T);
+      pc.qrows = static_cast<char*>(P.q_pf) + (size_t)c0 * P.qd * esz;
+      pc.orows = static_cast<char*>(P.o_pf) + (size_t)c0 * P.qd * esz;
+      ok = (P.hd == 128) ? stage_attn<T, 128>(pc, P.pf_layer) : stage_attn<T, 64>(pc, P.pf_layer);
+    }
+  } else if (P.kind == LS_PROG_PF_FINISH) {
+    PassCtx pc;
+    pc.qrows = P.qbuf; pc.orows = P.obuf;
+    pc.m = 1; pc.row0 = 0; pc.pos0 = P.n_tokens - 1; pc.l0 = pc.l1 = 0; pc.embed_src = false; pc.head = true;
+    ok = run_pass<T>(pc);
+    if (ok && TID == 0) {
+      LsState& st = ms->st;
+      const int keep_err = st.error;
+      st = LsState{};
+      st.error = keep_err;
+      st.pos = P.n_tokens; st.last = ms->r_tok[0]; st.n_gen = 1;
+      st.vmargin[0] = ms->r_margin[0];
+      if (P.out_tokens != nullptr && blockIdx.x == 0) P.out_tokens[0] = st.last;
+      if (st.last == P.eos || P.max_new <= 1) st.done = 1;
+    }
+    __syncthreads();
   } else if (P.kind == LS_PROG_DRAFT) {
     if (ms->st.pos + P.d + 1 > P.max_seq) {
       if (TID == 0) ms->st.error = 2;
@@ -1320,6 +1354,7 @@ __device__ __forceinline__ void program_body(const LsKParams& Pk) {
         if (ok) ok = do_verify<T>(P.E, P.d);
       } else {
         PassCtx pc;
+  pc.qrows = P.qbuf; pc.orows = P.obuf;
         pc.m = 1; pc.row0 = 0; pc.pos0 = ms->st.pos; pc.l0 = 0; pc.l1 = P.layers_used; pc.embed_src = true; pc.head = true;
         if (TID == 0) ms->tok[0] = clamp_tok(ms->st.last, P.vocab);
         __syncthreads();
@@ -1372,7 +1407,7 @@ extern "C" int ls_launch_copy(const void* src, void* dst, size_t bytes, hipStrea
 
 // ------------------------------------------------------------------------------------------
 static const void* kernel_for(int kind, int d, int dtype_is_bf16) {
-  const bool prompt = kind == LS_PROG_PREFILL || kind == LS_PROG_SCORE;
+  const bool prompt = kind == LS_PROG_PREFILL || kind == LS_PROG_SCORE || kind == LS_PROG_PF_ATTN || kind == LS_PROG_PF_FINISH;
   const bool greedy = kind == LS_PROG_GENERATE && d == 0;
   if (dtype_is_bf16)
     return prompt ? reinterpret_cast<const void*>(&ls_prompt_kernel<bf16_t>)

@@ -143,6 +143,41 @@ def test_large_cache_capacity_groups_attention_tiles(max_seq):
     gm.close()
 
 
+@pytest.mark.parametrize("name,n_prompt", [("c1", 150), ("c1-bf16", 131), ("gqa-hd128-bf16", 257), ("gqa2-f32", 64)])
+def test_prefill_hidden_states_and_cache(name, n_prompt):
+    """ls_prefill (the GEMM prompt pass for these lengths): per-layer hidden states of every prompt
+    row, the first token, and - through one draft/verify round on top of it - the KV cache."""
+    w = CASES[name].with_(n_prompt=n_prompt)
+    ws, prompt, om, gm = _setup(w, max_seq=n_prompt + 64)
+    hid = []
+    cache = om.new_cache(n_prompt + 64)
+    x = om.embed_tokens(prompt)
+    xl = om.run_layers(x, list(range(n_prompt)), cache, 0, w.model.n_layers, hid)
+    logits = om.head(xl[-1:])[0]
+    cap = gm.debug_capture(True)
+    gm.prefill(prompt)
+    pos, last, n_gen = gm.get_state()
+    assert (pos, n_gen) == (n_prompt, 1)
+    if O.top2_margin(logits) >= NEAR_TIE:
+        assert last == O.argmax_lowest(logits)
+    got = cap.cpu().numpy()[:, :n_prompt, :]
+    tol = 2e-2 if w.model.dtype == "bf16" else 1e-4
+    for l in range(w.model.n_layers):
+        assert rel_err_rows(got[l], hid[l]) < tol, l
+    gm.debug_capture(False)
+    ref = O.self_speculative(om, prompt, 8, w.exit_layer, w.draft_len)
+    if last == ref.tokens[0]:
+        r = ref.rounds[0]
+        gm.draft(w.exit_layer, w.draft_len)
+        gm.verify(w.exit_layer, w.draft_len)
+        D, V, _, _, n_acc = gm.peek_round(w.draft_len)
+        kd = next((i for i, g in enumerate(r.draft_margins) if g < NEAR_TIE), w.draft_len)
+        assert D[:kd] == r.draft[:kd]
+        if r.verify_margins[0] >= NEAR_TIE:
+            assert V[0] == r.verify[0]
+    gm.close()
+
+
 def test_exit_at_last_layer_accepts_everything_on_gpu():
     w = CASES["c1"]
     ws, prompt, om, gm = _setup(w)
