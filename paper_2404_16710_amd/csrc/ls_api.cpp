@@ -14,7 +14,7 @@
 #include "ls_internal.h"
 
 extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid, hipStream_t stream);
-extern "C" int ls_kernel_setup(int dtype_is_bf16, int* max_blocks_per_cu);
+extern "C" int ls_kernel_setup(int dtype_is_bf16, int hd, int* max_blocks_per_cu);
 extern "C" int ls_launch_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
 extern "C" int ls_prefill_layers(const LsPfParams* p, const LsLayerW* host_layers, int pos0, int M, hipStream_t s,
                                  int (*attn)(void*, int, int, int, hipStream_t), void* attn_ctx);
@@ -189,7 +189,7 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) { delete c; return LS_E_HIP; }
   c->n_cu = prop.multiProcessorCount;
   int nb = 0;
-  if (ls_kernel_setup(cfg->dtype == LS_BF16, &nb) != 0 || nb < 1) { delete c; return LS_E_HIP; }
+  if (ls_kernel_setup(cfg->dtype == LS_BF16, cfg->head_dim, &nb) != 0 || nb < 1) { delete c; return LS_E_HIP; }
   c->max_wg_per_cu = nb > 2 ? 2 : nb;
   c->wg_per_cu = c->max_wg_per_cu;
   if (const char* e = getenv("LS_WG_PER_CU")) {

@@ -1,0 +1,61 @@
+// Launches of the persistent decode kernels (one translation unit per (dtype, head_dim) variant
+// holds the kernels themselves) and the plain copy kernel used as a byte-counter reference.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include "ls_internal.h"
+
+#define LS_PROF_EVENTS 512
+
+extern "C" void ls_variant_kernels_bf16_hd128(const void** out);
+extern "C" void ls_variant_kernels_bf16_hd64(const void** out);
+extern "C" void ls_variant_kernels_f32_hd128(const void** out);
+extern "C" void ls_variant_kernels_f32_hd64(const void** out);
+
+// Plain copy, 16 bytes per thread per step: the known-size reference for hardware byte counters.
+__global__ __launch_bounds__(256) void ls_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+extern "C" int ls_launch_copy(const void* src, void* dst, size_t bytes, hipStream_t stream) {
+  ls_copy_kernel<<<dim3(2048), dim3(256), 0, stream>>>(static_cast<const uint4*>(src), static_cast<uint4*>(dst), bytes / 16);
+  return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+static const void* kernel_for(int kind, int d, int dtype_is_bf16, int hd) {
+  const void* k[3];
+  if (dtype_is_bf16) { if (hd == 128) ls_variant_kernels_bf16_hd128(k); else ls_variant_kernels_bf16_hd64(k); }
+  else { if (hd == 128) ls_variant_kernels_f32_hd128(k); else ls_variant_kernels_f32_hd64(k); }
+  const bool prompt = kind == LS_PROG_PREFILL || kind == LS_PROG_SCORE || kind == LS_PROG_PF_ATTN || kind == LS_PROG_PF_FINISH;
+  const bool greedy = kind == LS_PROG_GENERATE && d == 0;
+  return prompt ? k[0] : (greedy ? k[2] : k[1]);
+}
+
+extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid, hipStream_t stream) {
+  void* args[1] = {const_cast<LsKParams*>(p)};
+  // The grid is sized to be co-resident (occupancy x compute units) and the barrier wait is bounded,
+  // so an ordinary launch is used; LS_COOPERATIVE_LAUNCH=1 asks the runtime to guarantee residency.
+  static const bool coop = []() { const char* v = getenv("LS_COOPERATIVE_LAUNCH"); return v != nullptr && v[0] == '1'; }();
+  const size_t smem = LS_SMEM_BYTES + (p->prof != nullptr ? LS_PROF_EVENTS * 8 : 0);
+  const void* fn = kernel_for(p->kind, p->d, dtype_is_bf16, p->hd);
+  hipError_t e = coop ? hipLaunchCooperativeKernel(fn, dim3(grid), dim3(LS_THREADS), args, smem, stream)
+                      : hipLaunchKernel(fn, dim3(grid), dim3(LS_THREADS), args, smem, stream);
+  return e == hipSuccess ? 0 : (int)e;
+}
+
+extern "C" int ls_kernel_setup(int dtype_is_bf16, int hd, int* max_blocks_per_cu) {
+  int nb_min = 1 << 30;
+  for (int v = 0; v < 3; ++v) {
+    const void* fn = kernel_for(v == 0 ? (int)LS_PROG_PREFILL : (int)LS_PROG_GENERATE, v == 1 ? 0 : 1, dtype_is_bf16, hd);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LS_SMEM_BYTES + LS_PROF_EVENTS * 8);
+    if (e != hipSuccess) return (int)e;
+    int nb = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, LS_THREADS, LS_SMEM_BYTES + LS_PROF_EVENTS * 8);
+    if (e != hipSuccess) return (int)e;
+    if (nb < nb_min) nb_min = nb;
+  }
+  *max_blocks_per_cu = nb_min;
+  return 0;
+}
