@@ -113,6 +113,14 @@ def main() -> int:
     ach = b_ss / (ms_dec * 1e-3) / 1e9
     ach_ar = b_ar / (ar_ms_dec * 1e-3) / 1e9
 
+    # HBM bytes per decode launch from the committed counter profile of this very workload
+    # (FETCH_SIZE + WRITE_SIZE scaled by the copy-kernel reference); null for other workloads
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "decode_kernel_c2_hbm_traffic.md")
+    if a.config == "c2" and E == w.exit_layer and d == w.draft_len and os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = int(line.split(":")[1])
     out = {
         "metric": "generated tokens/s at batch 1, greedy self-speculative decoding (whole job: prefill + decode)",
         "value": round(value, 2), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -133,7 +141,7 @@ def main() -> int:
         "same_ids_as_full_greedy": bool(toks == ar_toks),
         "roofline": {"bound": "hbm", "kernel": "ls_decode_kernel<bf16> (one launch = all draft + tail + verify passes of a job)",
                      "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "bytes_per_launch": int(b_ss), "ms_per_launch": round(ms_dec, 3)},
     }
 
