@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 EXPORTS = (
     "ls_workspace_bytes", "ls_load_weights", "ls_prefill", "ls_draft", "ls_verify", "ls_generate",
     "ls_generate_early_exit", "ls_score", "ls_get_state", "ls_peek_round", "ls_debug_capture",
-    "ls_debug_timeline", "ls_debug_copy", "ls_set_launch", "ls_strerror", "ls_destroy",
+    "ls_debug_timeline", "ls_debug_copy", "ls_set_launch", "ls_set_exchange", "ls_strerror", "ls_destroy",
 )
 
 
@@ -108,6 +108,8 @@ def lib() -> C.CDLL:
     L.ls_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
     L.ls_set_launch.restype = C.c_int
     L.ls_set_launch.argtypes = [vp, i32]
+    L.ls_set_exchange.restype = C.c_int
+    L.ls_set_exchange.argtypes = [vp, i32]
     L.ls_strerror.restype = C.c_char_p
     L.ls_strerror.argtypes = [C.c_int]
     L.ls_destroy.restype = None
@@ -205,6 +207,9 @@ class LsModel:
         if g < 0:
             raise LsError(g, "ls_set_launch")
         return g
+
+    def set_exchange(self, max_tagged_rows: int) -> None:
+        _check(self.lib.ls_set_exchange(self.ctx, max_tagged_rows), "ls_set_exchange")
 
     def prefill(self, prompt: Sequence[int]) -> None:
         self._prompt = self._dev_i32(prompt)

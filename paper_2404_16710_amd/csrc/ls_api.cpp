@@ -24,7 +24,7 @@ namespace {
 
 struct Layout {
   size_t layers, rope_cos, rope_sin, kcache, vcache, xbuf, ssq, qbuf, obuf, actbuf, attn_part, attn_cnt, cand, bar,
-      state, x_pf, a_pf, q_pf, o_pf, act_pf, total;
+      state, xt, sst, qt, ot, kt, vt, at, ct, attn_cnt_ll, x_pf, a_pf, q_pf, o_pf, act_pf, total;
   int pf_rows;
 };
 
@@ -71,6 +71,16 @@ Layout make_layout(const ls_config* c) {
   L.cand = take(sizeof(float) * 4 * LS_ROWS * kMaxGrid);
   L.bar = take(4096);
   L.state = take(sizeof(LsState));
+  // tagged exchange: 8 bytes per 32-bit payload
+  L.xt = take(8 * (size_t)LS_ROWS * c->d_model);
+  L.sst = take(8 * (size_t)LS_ROWS * (c->d_model / 16));
+  L.qt = take(8 * (size_t)LS_ROWS * qd * esz / 4);
+  L.ot = take(8 * (size_t)LS_ROWS * qd * esz / 4);
+  L.kt = take(8 * (size_t)LS_ROWS * kvd * esz / 4);
+  L.vt = take(8 * (size_t)LS_ROWS * kvd * esz / 4);
+  L.at = take(8 * (size_t)LS_ROWS * c->ffn_dim * esz / 4);
+  L.ct = take(8 * (size_t)2 * kMaxGrid * LS_ROWS * 4);
+  L.attn_cnt_ll = take(sizeof(uint32_t) * c->n_kv_heads);
   L.pf_rows = c->max_seq < kPrefillRows ? c->max_seq : kPrefillRows;
   L.x_pf = take(sizeof(float) * L.pf_rows * c->d_model);
   L.a_pf = take(esz * L.pf_rows * c->d_model);
@@ -90,6 +100,7 @@ struct ls_ctx {
   LsKParams base;   // model + workspace part of the kernel parameters
   int n_cu, max_wg_per_cu, wg_per_cu, grid;
   bool prefilled, drafted;
+  bool poisoned;    // the device reported an error: exchange bookkeeping is rebuilt before the next prompt
   int draft_E, draft_d;
   int pos_bound;    // upper bound of the device-side position, for capacity checks
   hipEvent_t ev[3];
@@ -144,6 +155,17 @@ LsKParams program(const ls_ctx* c, int kind) {
 int read_state(ls_ctx* c, LsState* st, hipStream_t s) {
   if (hipMemcpyAsync(st, c->base.state, sizeof(LsState), hipMemcpyDeviceToHost, s) != hipSuccess) return LS_E_HIP;
   if (hipStreamSynchronize(s) != hipSuccess) return LS_E_HIP;
+  if (st->error) c->poisoned = true;
+  return LS_OK;
+}
+
+// After a device-side error the tags, counters and the error flag are unreliable: start them over
+// (counters, state and tagged buffers are contiguous in the workspace).
+int recover(ls_ctx* c, hipStream_t s) {
+  if (!c->poisoned) return LS_OK;
+  if (hipMemsetAsync(c->ws + c->lay.attn_cnt, 0, c->lay.x_pf - c->lay.attn_cnt, s) != hipSuccess) return LS_E_HIP;
+  c->poisoned = false;
+  c->prefilled = c->drafted = false;
   return LS_OK;
 }
 
@@ -182,6 +204,7 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   c->capture = nullptr;
   c->prof = nullptr; c->prof_cap = 0; c->prof_wg = 0;
   c->prefilled = c->drafted = false;
+  c->poisoned = false;
   c->pos_bound = 0;
 
   hipDeviceProp_t prop;
@@ -243,6 +266,13 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   p.cand = reinterpret_cast<float*>(c->ws + lay.cand);
   p.bar = reinterpret_cast<uint32_t*>(c->ws + lay.bar);
   p.state = reinterpret_cast<LsState*>(c->ws + lay.state);
+  p.xt = reinterpret_cast<uint64_t*>(c->ws + lay.xt); p.sst = reinterpret_cast<uint64_t*>(c->ws + lay.sst);
+  p.qt = reinterpret_cast<uint64_t*>(c->ws + lay.qt); p.ot = reinterpret_cast<uint64_t*>(c->ws + lay.ot);
+  p.kt = reinterpret_cast<uint64_t*>(c->ws + lay.kt); p.vt = reinterpret_cast<uint64_t*>(c->ws + lay.vt);
+  p.at = reinterpret_cast<uint64_t*>(c->ws + lay.at); p.ct = reinterpret_cast<uint64_t*>(c->ws + lay.ct);
+  p.attn_cnt_ll = reinterpret_cast<uint32_t*>(c->ws + lay.attn_cnt_ll);
+  p.ll_max_rows = 0;
+  if (const char* e = getenv("LS_TAGGED_ROWS")) { const int v = atoi(e); if (v >= 0 && v <= LS_ROWS) p.ll_max_rows = v; }
   p.spin_limit = 1 << 22;
   if (const char* e = getenv("LS_SPIN_LIMIT")) { const int v = atoi(e); if (v > 0) p.spin_limit = v; }
   p.q_pf = c->ws + lay.q_pf; p.o_pf = c->ws + lay.o_pf;
@@ -258,6 +288,14 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   c->gemm_prefill = true;
   if (const char* e = getenv("LS_PREFILL")) c->gemm_prefill = !(e[0] == 'r' || e[0] == '0');   // "rows": 16-row passes
   *out = c;
+  return LS_OK;
+}
+
+int ls_set_exchange(ls_ctx* c, int32_t max_tagged_rows) {
+  if (!c) return LS_E_ARG;
+  if (max_tagged_rows < 0 || max_tagged_rows > LS_ROWS) return LS_E_RANGE;
+  c->base.ll_max_rows = max_tagged_rows;
+  c->drafted = false;   // exit states of a pending draft may be in the other representation
   return LS_OK;
 }
 
@@ -306,8 +344,10 @@ int ls_prefill(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, void* str
   if (!c || !dev_prompt) return LS_E_ARG;
   if (n_prompt < 1) return LS_E_RANGE;
   if (n_prompt + 1 > c->cfg.max_seq) return LS_E_CAPACITY;
-  const int rc = enqueue_prefill(c, dev_prompt, n_prompt, c->cfg.n_layers, nullptr, -1, 0x7fffffff,
-                                 static_cast<hipStream_t>(stream));
+  int rc = recover(c, static_cast<hipStream_t>(stream));
+  if (rc != LS_OK) return rc;
+  rc = enqueue_prefill(c, dev_prompt, n_prompt, c->cfg.n_layers, nullptr, -1, 0x7fffffff,
+                       static_cast<hipStream_t>(stream));
   if (rc != LS_OK) return rc;
   c->prefilled = true; c->drafted = false; c->pos_bound = n_prompt;
   return LS_OK;
@@ -348,9 +388,11 @@ static int generate_impl(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt,
   if (layers_used < 1 || layers_used > c->cfg.n_layers) return LS_E_RANGE;
   if ((long)n_prompt + max_new + d + 1 > c->cfg.max_seq) return LS_E_CAPACITY;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  int rc = recover(c, s);
+  if (rc != LS_OK) return rc;
   if (hipMemsetAsync(dev_out, 0xFF, sizeof(int32_t) * max_new, s) != hipSuccess) return LS_E_HIP;
   if (hipEventRecord(c->ev[0], s) != hipSuccess) return LS_E_HIP;
-  int rc = enqueue_prefill(c, dev_prompt, n_prompt, layers_used, dev_out, eos, max_new, s);
+  rc = enqueue_prefill(c, dev_prompt, n_prompt, layers_used, dev_out, eos, max_new, s);
   if (rc != LS_OK) return rc;
   if (hipEventRecord(c->ev[1], s) != hipSuccess) return LS_E_HIP;
   LsKParams g = program(c, LS_PROG_GENERATE);

@@ -7,6 +7,7 @@
 
 #define LS_THREADS 256          // workgroup size of the persistent kernel (4 wavefronts)
 #define LS_WAVES (LS_THREADS / 64)
+#define LS_SLOTS 4              // 256-byte weight blocks per wave kept in flight (per tile: LS_SLOTS / tiles)
 #define LS_ROWS 16              // rows per pass (MFMA N dimension)
 #define LS_ATTN_TILE 64         // KV positions per attention work item
 #define LS_ACT_BYTES (128 * 1024) // LDS bytes for staged matmul inputs
@@ -16,6 +17,14 @@
 
 struct LsLayerW {
   const void *wq, *wk, *wv, *wo, *wg, *wu, *wd, *attn_norm, *ffn_norm;
+};
+
+// Bookkeeping of the tagged exchange (see ls_kernels.inc); survives prefills and launches.
+struct LsExch {
+  uint32_t seq;             // tag of the most recent stage that published tagged data
+  uint32_t attn_base;       // completed attention items per kv head so far (monotone counters)
+  uint32_t cand_par;        // which of the two candidate buffers the next head stage writes
+  uint32_t xtag[LS_ROWS];   // tag of the current contents of each tagged residual row (0: none)
 };
 
 // Decoding state.  One copy lives in device memory (read by the host through ls_get_state /
@@ -35,6 +44,7 @@ struct LsState {
   int32_t V[LS_ROWS];
   float dmargin[LS_ROWS];
   float vmargin[LS_ROWS];
+  LsExch ex;
 };
 
 enum LsProgramKind {
@@ -75,6 +85,16 @@ struct LsKParams {
   int32_t *out_tokens;
   float *out_margin;
   int32_t spin_limit;
+  // tagged exchange: 8-byte words (32-bit payload, 32-bit tag) that consumers poll instead of
+  // waiting at a grid barrier; used by passes of at most ll_max_rows rows
+  uint64_t *xt;                     // [16][dm]      residual rows, fp32 payload
+  uint64_t *sst;                    // [16][dm/16]   their per-tile sums of squares
+  uint64_t *qt, *ot;                // [16][qd*esz/4]  q rows / attention output rows (model dtype, packed)
+  uint64_t *kt, *vt;                // [16][kvd*esz/4] k and v rows of the pass
+  uint64_t *at;                     // [16][ffn*esz/4] SwiGLU rows
+  uint64_t *ct;                     // [2][grid][16][4] argmax candidates, two buffers used alternately
+  uint32_t *attn_cnt_ll;            // [nkv] monotone completion counters
+  int32_t ll_max_rows;
   // GEMM prefill: q rows / attention output rows of the prompt chunk, and which layer / rows
   void *q_pf, *o_pf;
   int32_t pf_layer, pf_pos0;

@@ -58,6 +58,35 @@ def test_generate_matches_oracle_and_full_greedy(name):
     gm.close()
 
 
+@pytest.mark.parametrize("name", ["c1", "c1-bf16", "gqa-hd128-bf16", "gqa2-f32"])
+def test_tagged_exchange_gives_the_same_bits_as_barriers(name):
+    """ls_set_exchange: polled, tagged hand-over between stages for passes of at most r rows, grid
+    barriers for the others.  Every setting must give identical tokens, round statistics, per-round
+    drafts / margins and hidden states; the barrier setting is the one checked against the oracle above."""
+    w = CASES[name]
+    ws, prompt, om, gm = _setup(w)
+    cap = gm.debug_capture(True)
+    base = None
+    for rows in (0, 1, w.draft_len, 16):
+        gm.set_exchange(rows)
+        cap.zero_()
+        toks, st = gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
+        hid = cap.cpu().numpy().copy()
+        ar, _ = gm.generate(prompt, w.n_new, 0, 0)
+        gm.prefill(prompt)                      # one round through the step-by-step calls
+        gm.draft(w.exit_layer, w.draft_len)
+        gm.verify(w.exit_layer, w.draft_len)
+        rnd = gm.peek_round(w.draft_len)
+        got = (toks, ar, (st.rounds, st.drafted, st.accepted, st.generated), rnd)
+        if base is None:
+            base, base_hid = got, hid
+            assert toks == ar
+        else:
+            assert got == base, rows
+            assert np.array_equal(hid, base_hid), rows
+    gm.close()
+
+
 @pytest.mark.parametrize("name", ["c1", "c1-bf16", "gqa-hd128-bf16"])
 def test_teacher_forced_scores_match_oracle(name):
     """Full-model argmax of every row of prompt+output, given the oracle's own sequence: covers every

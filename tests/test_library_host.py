@@ -66,7 +66,8 @@ def test_null_and_misaligned_arguments_are_rejected_without_a_gpu():
     assert lib.ls_load_weights(C.byref(cfg), C.byref(w), C.c_void_p(257), 1 << 30, C.byref(ctx)) == -1
     for fn, args in (("ls_prefill", (None, None, 4, None)), ("ls_draft", (None, 1, 1, None)),
                      ("ls_verify", (None, 1, 1, None)), ("ls_get_state", (None, None, None, None, None)),
-                     ("ls_debug_capture", (None, None)), ("ls_set_launch", (None, 1))):
+                     ("ls_debug_capture", (None, None)), ("ls_set_launch", (None, 1)),
+                     ("ls_set_exchange", (None, 1))):
         assert getattr(lib, fn)(*args) == -1, fn
     assert b"capacity" in lib.ls_strerror(-3) and b"ok" == lib.ls_strerror(0)
     lib.ls_destroy(None)                                     # harmless
