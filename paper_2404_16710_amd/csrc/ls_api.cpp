@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdint>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -62,7 +63,7 @@ Layout make_layout(const ls_config* c) {
   L.kcache = take(esz * c->n_layers * kvd * c->max_seq);
   L.vcache = take(esz * c->n_layers * kvd * c->max_seq);
   L.xbuf = take(sizeof(float) * LS_ROWS * c->d_model);
-  L.ssq = take(sizeof(float) * LS_ROWS * (c->d_model / 16));
+  L.ssq = take(sizeof(float) * LS_ROWS * (c->d_model / 8));   // per-tile sums of squares, tiles of 8 rows or more
   L.qbuf = take(esz * LS_ROWS * qd);
   L.obuf = take(esz * LS_ROWS * qd);
   L.actbuf = take(esz * LS_ROWS * c->ffn_dim);
@@ -73,7 +74,7 @@ Layout make_layout(const ls_config* c) {
   L.state = take(sizeof(LsState));
   // tagged exchange: 8 bytes per 32-bit payload
   L.xt = take(8 * (size_t)LS_ROWS * c->d_model);
-  L.sst = take(8 * (size_t)LS_ROWS * (c->d_model / 16));
+  L.sst = take(8 * (size_t)LS_ROWS * (c->d_model / 8));
   L.qt = take(8 * (size_t)LS_ROWS * qd * esz / 4);
   L.ot = take(8 * (size_t)LS_ROWS * qd * esz / 4);
   L.kt = take(8 * (size_t)LS_ROWS * kvd * esz / 4);
@@ -114,20 +115,33 @@ struct ls_ctx {
 
 namespace {
 
-int choose_nt(int units, int grid, bool pairs) {
-  // tiles a workgroup multiplies at once: 2 if that still leaves at least `grid` groups
-  if (pairs) return 2;
-  return (units + 1) / 2 >= grid ? 2 : 1;
+// Rows per weight tile (8, 12 or 16) for a matrix with `rows` output rows spread over `grid`
+// workgroups in whole tiles: the size that gives the busiest workgroup the fewest rows (the largest
+// such size: fewer, fuller tiles).
+int choose_tile_rows(int rows, int grid) {
+  int best = 16, best_rows = INT32_MAX;
+  for (int gs = 16; gs >= 8; gs -= 4) {
+    const int tiles = (rows + gs - 1) / gs;
+    const int most = (tiles + grid - 1) / grid * gs;
+    if (most < best_rows) { best_rows = most; best = gs; }
+  }
+  return best;
 }
 
 void set_decomposition(ls_ctx* c) {
   const ls_config& g = c->cfg;
-  const int pph = g.head_dim / 32;
-  const int qkv_items = (g.n_q_heads + g.n_kv_heads) * pph + g.n_kv_heads * g.head_dim / 32;
-  c->base.nt_qkv = choose_nt(qkv_items, c->grid, true);
-  c->base.nt_o = choose_nt(g.d_model / 16, c->grid, false);
-  c->base.nt_gu = choose_nt(g.ffn_dim / 16, c->grid, true);
-  c->base.nt_down = c->base.nt_o;
+  // O / down projections: smaller tiles only when some workgroup would otherwise get two (more
+  // workgroups with a tile means more readers of the broadcast input rows, which costs as much as
+  // the shorter weight stream gains)
+  c->base.gs_x = g.d_model / 16 <= c->grid ? 16 : choose_tile_rows(g.d_model, c->grid);
+  c->base.gs_ffn = choose_tile_rows(g.ffn_dim, c->grid);
+  if (const char* e = getenv("LS_TILE_ROWS")) {   // "x,ffn" (tuning aid)
+    int a = 0, b = 0;
+    if (sscanf(e, "%d,%d", &a, &b) == 2 && (a == 8 || a == 12 || a == 16) && (b == 8 || b == 12 || b == 16)) {
+      c->base.gs_x = a; c->base.gs_ffn = b;
+    }
+  }
+  c->base.ssq_nt = (g.d_model + c->base.gs_x - 1) / c->base.gs_x;
   // attention work items: (kv head, C consecutive 64-position tiles), C the smallest count for
   // which a full cache gives at most one item per workgroup
   const int max_tiles = (g.max_seq + LS_ATTN_TILE - 1) / LS_ATTN_TILE;
@@ -327,6 +341,7 @@ static int enqueue_prefill(ls_ctx* c, const int32_t* dev_prompt, int32_t n_promp
     return launch(c, p, s);
   }
   LsPfParams f = c->pf;
+  f.gs_x = c->base.gs_x;
   f.tokens = dev_prompt; f.layers_used = layers_used; f.capture = c->capture;
   int last_rows = 0;
   for (int pos0 = 0; pos0 < n_prompt; pos0 += c->lay.pf_rows) {

@@ -67,7 +67,7 @@ struct LsKParams {
   // workspace
   void *kcache, *vcache;            // [L][nkv][max_seq][hd]
   float *xbuf;                      // [16][dm]  residual rows = exit-state rows
-  float *ssq;                       // [16][dm/16] sum of squares of xbuf rows, per 16-wide tile
+  float *ssq;                       // [16][ssq_nt] sum of squares of xbuf rows, per gs_x-wide tile
   void *qbuf, *obuf, *actbuf;       // [16][qd], [16][qd], [16][ffn]
   float *attn_part;                 // [nkv][max_tiles][64][hd+2]
   uint32_t *attn_cnt;               // [nkv]
@@ -77,8 +77,10 @@ struct LsKParams {
   uint32_t *bar;                    // grid barrier counter
   LsState *state;
   float *capture;                   // [L][max_seq][dm] or null
-  // decomposition: tiles a workgroup processes at once in each stage
-  int32_t nt_qkv, nt_o, nt_gu, nt_down;
+  // decomposition: output rows per weight tile in the O / down projections (gs_x) and in the
+  // gate / up projections (gs_ffn): 8, 12 or 16, chosen so that the workgroup with the most rows
+  // has as few as possible; ssq_nt = ceil(dm / gs_x) sums of squares per residual row
+  int32_t gs_x, gs_ffn, ssq_nt;
   // program
   int32_t kind, E, d, max_new, eos, n_tokens, layers_used;
   const int32_t *tokens;
@@ -88,7 +90,7 @@ struct LsKParams {
   // tagged exchange: 8-byte words (32-bit payload, 32-bit tag) that consumers poll instead of
   // waiting at a grid barrier; used by passes of at most ll_max_rows rows
   uint64_t *xt;                     // [16][dm]      residual rows, fp32 payload
-  uint64_t *sst;                    // [16][dm/16]   their per-tile sums of squares
+  uint64_t *sst;                    // [16][ssq_nt]  their per-tile sums of squares
   uint64_t *qt, *ot;                // [16][qd*esz/4]  q rows / attention output rows (model dtype, packed)
   uint64_t *kt, *vt;                // [16][kvd*esz/4] k and v rows of the pass
   uint64_t *at;                     // [16][ffn*esz/4] SwiGLU rows
@@ -106,6 +108,7 @@ struct LsKParams {
 // Parameters of the GEMM prefill (host side launches; see ls_prefill.hip).
 struct LsPfParams {
   int32_t is_bf16, dm, qd, kvd, ffn, vocab, hd, nkv, max_seq, layers_used;
+  int32_t gs_x;                // columns per sum of squares of a residual row (LsKParams::gs_x)
   float eps;
   const int32_t *tokens;
   const void *embed;

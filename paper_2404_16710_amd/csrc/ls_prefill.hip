@@ -72,12 +72,12 @@ __global__ __launch_bounds__(256) void pf_rmsnorm_kernel(const float* x, const T
   for (int k = threadIdx.x; k < dm; k += 256) PT<T>::st(a + (size_t)m * dm + k, (xr[k] * r) * PT<T>::ld(gain + k));
 }
 
-// The last prompt row goes to row 0 of the decode residual buffer, with the per-16-column sums of
-// squares its RMSNorm needs; the head then runs in the decode kernel.
-__global__ __launch_bounds__(256) void pf_finish_kernel(const float* xrow, float* xbuf, float* ssq, int dm) {
-  for (int t = threadIdx.x; t < dm / 16; t += 256) {
+// The last prompt row goes to row 0 of the decode residual buffer, with the sums of squares per
+// gs columns its RMSNorm needs; the head then runs in the decode kernel.
+__global__ __launch_bounds__(256) void pf_finish_kernel(const float* xrow, float* xbuf, float* ssq, int dm, int gs) {
+  for (int t = threadIdx.x; t * gs < dm; t += 256) {
     float s = 0.f;
-    for (int j = 0; j < 16; ++j) { const float v = xrow[t * 16 + j]; xbuf[t * 16 + j] = v; s += v * v; }
+    for (int j = 0; j < gs && t * gs + j < dm; ++j) { const float v = xrow[t * gs + j]; xbuf[t * gs + j] = v; s += v * v; }
     ssq[t] = s;
   }
 }
@@ -273,6 +273,6 @@ extern "C" int ls_prefill_layers(const LsPfParams* p, const LsLayerW* host_layer
 }
 
 extern "C" int ls_prefill_finish(const LsPfParams* p, int last_row, hipStream_t s) {
-  pf_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(p->x_pf + (size_t)last_row * p->dm, p->xbuf, p->ssq, p->dm);
+  pf_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(p->x_pf + (size_t)last_row * p->dm, p->xbuf, p->ssq, p->dm, p->gs_x);
   return hipGetLastError() == hipSuccess ? 0 : 1;
 }
