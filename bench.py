@@ -54,6 +54,8 @@ def main() -> int:
     ap.add_argument("--draft", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-new", type=int, default=24)
+    ap.add_argument("--sweep", action="store_true",
+                    help="also run the workload's (exit layer, draft length) grid and add it to the JSON line")
     ap.add_argument("--wg-per-cu", type=int, default=0)
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run the library's plain copy kernel over this many MiB (byte-counter reference)")
@@ -171,6 +173,28 @@ def main() -> int:
             "ids_match_gpu_until_near_tie": int(next((i for i, (x, y) in enumerate(zip(toks, ref.tokens)) if x != y), n_s)),
         }
     model.close()
+    if a.sweep and w.sweep_exit_layers:
+        # the (E, d) grid of the workload: weights are regenerated per E (the scaled layers follow E);
+        # full-model greedy is timed once per E on those weights
+        del model, weights
+        out["sweep"] = []
+        for Es in w.sweep_exit_layers:
+            ws = W.make_weights(w, exit_layer=Es, threads=min(16, len(os.sched_getaffinity(0))))
+            mod = LsModel(m, ws, max_seq=w.n_prompt + w.n_new + 16 + 1)
+            mod.generate(prompt, w.n_new, 0, 0)
+            ar_t, ar_s = mod.generate(prompt, w.n_new, 0, 0)
+            for ds in w.sweep_draft_lens:
+                mod.generate(prompt, w.n_new, Es, ds)
+                tk, s_ = mod.generate(prompt, w.n_new, Es, ds)
+                row = {"exit_layer": Es, "draft_len": ds, "acceptance": round(s_.acceptance, 4), "rounds": s_.rounds,
+                       "decode_tokens_per_s": round((w.n_new - 1) / (s_.ms_decode * 1e-3), 2),
+                       "full_greedy_decode_tokens_per_s": round((w.n_new - 1) / (ar_s.ms_decode * 1e-3), 2),
+                       "speedup_vs_full_greedy": round(ar_s.ms_decode / s_.ms_decode, 3),
+                       "same_ids_as_full_greedy": bool(tk == ar_t)}
+                out["sweep"].append(row)
+                print(f"[bench] sweep {row}", file=sys.stderr, flush=True)
+            mod.close()
+            del mod, ws
     print(json.dumps(out), flush=True)
     return 0
 
