@@ -111,6 +111,7 @@ struct ls_ctx {
   std::vector<LsLayerW> host_layers;
   LsPfParams pf;
   bool gemm_prefill;
+  bool rows_attn;   // prompt attention through the decode kernel's attention stage (LS_PREFILL_ATTN=rows)
 };
 
 namespace {
@@ -301,6 +302,8 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   f.o_pf = c->ws + lay.o_pf; f.act_pf = c->ws + lay.act_pf; f.xbuf = p.xbuf; f.ssq = p.ssq;
   c->gemm_prefill = true;
   if (const char* e = getenv("LS_PREFILL")) c->gemm_prefill = !(e[0] == 'r' || e[0] == '0');   // "rows": 16-row passes
+  c->rows_attn = false;
+  if (const char* e = getenv("LS_PREFILL_ATTN")) c->rows_attn = e[0] == 'r';
   *out = c;
   return LS_OK;
 }
@@ -346,7 +349,7 @@ static int enqueue_prefill(ls_ctx* c, const int32_t* dev_prompt, int32_t n_promp
   int last_rows = 0;
   for (int pos0 = 0; pos0 < n_prompt; pos0 += c->lay.pf_rows) {
     const int M = n_prompt - pos0 < c->lay.pf_rows ? n_prompt - pos0 : c->lay.pf_rows;
-    if (ls_prefill_layers(&f, c->host_layers.data(), pos0, M, s, pf_attn_cb, c) != 0) return LS_E_HIP;
+    if (ls_prefill_layers(&f, c->host_layers.data(), pos0, M, s, c->rows_attn ? pf_attn_cb : nullptr, c) != 0) return LS_E_HIP;
     last_rows = M;
   }
   if (ls_prefill_finish(&f, last_rows - 1, s) != 0) return LS_E_HIP;

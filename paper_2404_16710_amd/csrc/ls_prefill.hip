@@ -1,9 +1,9 @@
 // Prompt pass (prefill) for gfx950: all rows of the prompt go through each layer together, so the
 // projections are real GEMMs (M = prompt rows) on the MFMA units instead of 16-row passes that
 // re-read every weight.  Per layer:
-//   RMSNorm -> Q/K/V GEMMs (+RoPE, KV append) -> causal attention (the decode attention stage, in
-//   blocks of query rows over the shared cache) -> O GEMM (+residual) -> RMSNorm ->
-//   gate/up GEMM (+SwiGLU) -> down GEMM (+residual).
+//   RMSNorm -> Q/K/V GEMMs (+RoPE, KV append) -> causal attention over the shared cache (MFMA,
+//   running softmax over K/V tiles) -> O GEMM (+residual) -> RMSNorm -> gate/up GEMM (+SwiGLU) ->
+//   down GEMM (+residual).
 // Rounding points are the ones of the decode path: RMSNorm output, q/k after RoPE, v, the
 // attention output and the SwiGLU output are stored in the model dtype; the residual stream and
 // all accumulation are fp32.
@@ -232,6 +232,201 @@ hipError_t launch_gemm(const PfGemm& g, hipStream_t s) {
   return hipGetLastError();
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Causal attention of the prompt rows on the MFMA units.  One workgroup = 64 query rows of one
+// query head (a wave = 16 of them); K/V tiles of TK positions are staged in LDS (V transposed, so
+// that both operands of both products are contiguous along the contracted index) and folded in
+// with a running softmax.  Everything is computed transposed:
+//   S^T = K . Q^T   (rows: keys,  columns: the wave's 16 queries)
+//   O^T = V^T . P^T (rows: dims,  columns: the same queries)
+// so a lane keeps one query's statistics: lane (c = lane & 15, g = lane >> 4) holds S^T rows
+// 4g..4g+3 of column c for each 16-key block, which are exactly the slots 8g..8g+7 of the P^T
+// operand when a 32-key half is numbered (block 0: keys 4g..4g+3, block 1: keys 16+4g..16+4g+3);
+// the V^T operand is read from LDS in that order.  Probabilities stay fp32 in effect: for bf16
+// models P is fed as a bf16 head plus a bf16 remainder (two products), scores, statistics and the
+// output accumulate in fp32; the output is rounded to the model dtype on store, like the decode path.
+template <typename T> struct AT;
+template <> struct AT<bf16_t> {
+  struct Op { uint4 v; };
+  static __device__ __forceinline__ Op ld8(const bf16_t* p) { Op o; o.v = *reinterpret_cast<const uint4*>(p); return o; }
+  static __device__ __forceinline__ Op ld44(const bf16_t* p0, const bf16_t* p1) {
+    const uint2 a = *reinterpret_cast<const uint2*>(p0), b = *reinterpret_cast<const uint2*>(p1);
+    Op o; o.v = make_uint4(a.x, a.y, b.x, b.y); return o;
+  }
+  static __device__ __forceinline__ void mma(f32x4& acc, const Op& a, const Op& b) {
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a.v), __builtin_bit_cast(bf16x8, b.v), acc, 0, 0, 0);
+  }
+  static __device__ __forceinline__ void mma_p(f32x4& acc, const Op& a, const float* p) {
+    uint32_t hi[8], lo[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { hi[j] = f2bf(p[j]); lo[j] = f2bf(p[j] - bf2f(hi[j])); }
+    Op h, l;
+    h.v = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16), hi[6] | (hi[7] << 16));
+    l.v = make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16), lo[6] | (lo[7] << 16));
+    mma(acc, a, h);
+    mma(acc, a, l);
+  }
+  static __device__ __forceinline__ void scatter(bf16_t* vt, int stride, const uint4& v) {  // 8 elements, one per row
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vt[e * stride] = (bf16_t)((w[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu);
+  }
+};
+template <> struct AT<float> {
+  struct Op { float f[8]; };
+  static __device__ __forceinline__ Op ld8(const float* p) {
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    Op o; o.f[0] = a.x; o.f[1] = a.y; o.f[2] = a.z; o.f[3] = a.w; o.f[4] = b.x; o.f[5] = b.y; o.f[6] = b.z; o.f[7] = b.w; return o;
+  }
+  static __device__ __forceinline__ Op ld44(const float* p0, const float* p1) {
+    const float4 a = *reinterpret_cast<const float4*>(p0), b = *reinterpret_cast<const float4*>(p1);
+    Op o; o.f[0] = a.x; o.f[1] = a.y; o.f[2] = a.z; o.f[3] = a.w; o.f[4] = b.x; o.f[5] = b.y; o.f[6] = b.z; o.f[7] = b.w; return o;
+  }
+  static __device__ __forceinline__ void mma(f32x4& acc, const Op& a, const Op& b) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.f[j], b.f[j], acc, 0, 0, 0);
+  }
+  static __device__ __forceinline__ void mma_p(f32x4& acc, const Op& a, const float* p) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.f[j], p[j], acc, 0, 0, 0);
+  }
+  static __device__ __forceinline__ void scatter(float* vt, int stride, const uint4& v) {   // 4 elements
+    vt[0] = __uint_as_float(v.x); vt[stride] = __uint_as_float(v.y);
+    vt[2 * stride] = __uint_as_float(v.z); vt[3 * stride] = __uint_as_float(v.w);
+  }
+};
+
+template <typename T, int HD>
+__global__ __launch_bounds__(256) void pf_attn_kernel(const T* __restrict__ q, T* __restrict__ o,
+                                                      const T* __restrict__ kc, const T* __restrict__ vc, int M,
+                                                      int pos0, int qd, int G, int max_seq, float scale) {
+  constexpr int EPV = 16 / (int)sizeof(T);          // elements per 16 bytes
+  constexpr int TK = sizeof(T) == 2 ? 64 : 32;      // positions per K/V tile
+  constexpr int KB16 = TK / 16, HF = TK / 32, KS = HD / 32, DB = HD / 16;
+  constexpr int KROW = HD + EPV;                    // padded rows: conflict-free 16-byte reads down a column of rows
+  constexpr int VROW = TK + 4;
+  constexpr int UPR = HD / EPV;                     // 16-byte units per K/V row
+  __shared__ __align__(16) T Ks[TK * KROW];
+  __shared__ __align__(16) T VTs[HD * VROW];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, cq = lane & 15, g = lane >> 4;
+  const int qb = (int)gridDim.x - 1 - (int)blockIdx.x;   // blocks with the most tiles start first
+  const int h = blockIdx.y, c = h / G;
+  const int row = qb * 64 + wave * 16 + cq;
+  const bool rowok = row < M;
+  const int qpos = pos0 + row;
+  const T* kbase = kc + (size_t)c * max_seq * HD;
+  const T* vbase = vc + (size_t)c * max_seq * HD;
+  typename AT<T>::Op qop[KS];
+  {
+    const T* qp = q + (size_t)(rowok ? row : 0) * qd + h * HD + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qop[ks] = AT<T>::ld8(qp + 32 * ks);
+  }
+  f32x4 oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) oacc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float mrun = -INFINITY, lrun = 0.f;
+  const int last_row = qb * 64 + 63 < M - 1 ? qb * 64 + 63 : M - 1;
+  const int nt = (pos0 + last_row) / TK + 1;
+  const int written = pos0 + M;                     // cache positions [0, written) hold this layer's K and V
+  const int wave_last = pos0 + qb * 64 + wave * 16 + 15;
+  for (int t = 0; t < nt; ++t) {
+    const int kp0 = t * TK;
+    __syncthreads();
+    for (int u = tid; u < TK * UPR; u += 256) {
+      const int key = u / UPR, part = u - key * UPR;
+      const int kp = kp0 + key;
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (kp < written) v = *reinterpret_cast<const uint4*>(kbase + (size_t)kp * HD + part * EPV);
+      *reinterpret_cast<uint4*>(Ks + key * KROW + part * EPV) = v;
+    }
+    for (int u = tid; u < TK * UPR; u += 256) {
+      const int part = u / TK, key = u - part * TK;
+      const int kp = kp0 + key;
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);            // zeros past the end: 0 * (stale bits) must not give NaN
+      if (kp < written) v = *reinterpret_cast<const uint4*>(vbase + (size_t)kp * HD + part * EPV);
+      AT<T>::scatter(VTs + (part * EPV) * VROW + key, VROW, v);
+    }
+    __syncthreads();
+    if (kp0 > wave_last) continue;                  // wholly in this wave's future (the barriers above still match)
+    f32x4 s[KB16];
+#pragma unroll
+    for (int kb = 0; kb < KB16; ++kb) {
+      s[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        AT<T>::mma(s[kb], AT<T>::ld8(Ks + (kb * 16 + cq) * KROW + 32 * ks + 8 * g), qop[ks]);
+    }
+    float sv[KB16][4];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < KB16; ++kb) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int kp = kp0 + kb * 16 + 4 * g + j;
+        sv[kb][j] = kp <= qpos ? s[kb][j] * scale : -INFINITY;
+        mx = fmaxf(mx, sv[kb][j]);
+      }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float mnew = fmaxf(mrun, mx);
+    const float alpha = mrun == -INFINITY ? 0.f : expf(mrun - mnew);
+    float psum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < KB16; ++kb) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        sv[kb][j] = sv[kb][j] == -INFINITY ? 0.f : expf(sv[kb][j] - mnew);
+        psum += sv[kb][j];
+      }
+    }
+    psum += __shfl_xor(psum, 16);
+    psum += __shfl_xor(psum, 32);
+    lrun = lrun * alpha + psum;
+    mrun = mnew;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      oacc[db][0] *= alpha; oacc[db][1] *= alpha; oacc[db][2] *= alpha; oacc[db][3] *= alpha;
+    }
+#pragma unroll
+    for (int hf = 0; hf < HF; ++hf) {
+      const float pp[8] = {sv[2 * hf][0], sv[2 * hf][1], sv[2 * hf][2], sv[2 * hf][3],
+                           sv[2 * hf + 1][0], sv[2 * hf + 1][1], sv[2 * hf + 1][2], sv[2 * hf + 1][3]};
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const T* vt = VTs + (db * 16 + cq) * VROW + 32 * hf + 4 * g;
+        AT<T>::mma_p(oacc[db], AT<T>::ld44(vt, vt + 16), pp);
+      }
+    }
+  }
+  if (rowok) {
+    const float inv = 1.0f / lrun;
+    T* op = o + (size_t)row * qd + h * HD + 4 * g;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) PT<T>::st(op + db * 16 + j, oacc[db][j] * inv);
+    }
+  }
+}
+
+template <typename T>
+hipError_t launch_attn(const LsPfParams& p, int layer, int pos0, int M, hipStream_t s) {
+  const int nq = p.qd / p.hd, G = nq / p.nkv;
+  const size_t lofs = (size_t)layer * p.nkv * p.max_seq * p.hd;
+  const T* kc = static_cast<const T*>(p.kcache) + lofs;
+  const T* vc = static_cast<const T*>(p.vcache) + lofs;
+  const float scale = (float)(1.0 / sqrt((double)p.hd));
+  dim3 grid((M + 63) / 64, nq);
+  if (p.hd == 128)
+    pf_attn_kernel<T, 128><<<grid, dim3(256), 0, s>>>(static_cast<const T*>(p.q_pf), static_cast<T*>(p.o_pf), kc, vc, M, pos0, p.qd, G, p.max_seq, scale);
+  else
+    pf_attn_kernel<T, 64><<<grid, dim3(256), 0, s>>>(static_cast<const T*>(p.q_pf), static_cast<T*>(p.o_pf), kc, vc, M, pos0, p.qd, G, p.max_seq, scale);
+  return hipGetLastError();
+}
+
 template <typename T>
 int run_layers(const LsPfParams& p, const LsLayerW* lw, int pos0, int M, hipStream_t s,
                int (*attn)(void*, int, int, int, hipStream_t), void* attn_ctx) {
@@ -249,7 +444,11 @@ int run_layers(const LsPfParams& p, const LsLayerW* lw, int pos0, int M, hipStre
     if (launch_gemm<T, EPI_ROPE_K>(g, s) != hipSuccess) return 1;
     g.W = W.wv; g.N = kvd; g.out = p.vcache;
     if (launch_gemm<T, EPI_V>(g, s) != hipSuccess) return 1;
-    if (attn(attn_ctx, l, pos0, M, s) != 0) return 1;
+    if (attn != nullptr) {          // attention through the decode kernel's stage (comparison aid)
+      if (attn(attn_ctx, l, pos0, M, s) != 0) return 1;
+    } else if (launch_attn<T>(p, l, pos0, M, s) != hipSuccess) {
+      return 1;
+    }
     g.A = p.o_pf; g.lda = qd; g.K = qd; g.W = W.wo; g.N = dm; g.x = p.x_pf; g.capture = nullptr;
     if (launch_gemm<T, EPI_RESID>(g, s) != hipSuccess) return 1;
     pf_rmsnorm_kernel<T><<<dim3(M), dim3(256), 0, s>>>(p.x_pf, static_cast<const T*>(W.ffn_norm), static_cast<T*>(p.a_pf), dm, p.eps);
@@ -264,8 +463,9 @@ int run_layers(const LsPfParams& p, const LsLayerW* lw, int pos0, int M, hipStre
 
 }  // namespace
 
-// Runs layers 0..layers_used-1 over rows [pos0, pos0+M) of the prompt (M <= pf_rows).  `attn` is
-// called once per layer to enqueue the attention of those rows (q rows in q_pf, output to o_pf).
+// Runs layers 0..layers_used-1 over rows [pos0, pos0+M) of the prompt (M <= pf_rows).  `attn`, when
+// not null, is called once per layer to enqueue the attention of those rows instead of the MFMA
+// attention kernel (q rows in q_pf, output to o_pf).
 extern "C" int ls_prefill_layers(const LsPfParams* p, const LsLayerW* host_layers, int pos0, int M, hipStream_t s,
                                  int (*attn)(void*, int, int, int, hipStream_t), void* attn_ctx) {
   return p->is_bf16 ? run_layers<bf16_t>(*p, host_layers, pos0, M, s, attn, attn_ctx)
