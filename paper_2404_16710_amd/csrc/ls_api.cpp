@@ -17,8 +17,7 @@
 extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid, hipStream_t stream);
 extern "C" int ls_kernel_setup(int dtype_is_bf16, int hd, int* max_blocks_per_cu);
 extern "C" int ls_launch_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
-extern "C" int ls_prefill_layers(const LsPfParams* p, const LsLayerW* host_layers, int pos0, int M, hipStream_t s,
-                                 int (*attn)(void*, int, int, int, hipStream_t), void* attn_ctx);
+extern "C" int ls_prefill_layers(const LsPfParams* p, const LsLayerW* host_layers, int pos0, int M, hipStream_t s);
 extern "C" int ls_prefill_finish(const LsPfParams* p, int last_row, hipStream_t s);
 
 namespace {
@@ -111,7 +110,6 @@ struct ls_ctx {
   std::vector<LsLayerW> host_layers;
   LsPfParams pf;
   bool gemm_prefill;
-  bool rows_attn;   // prompt attention through the decode kernel's attention stage (LS_PREFILL_ATTN=rows)
 };
 
 namespace {
@@ -290,7 +288,6 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   if (const char* e = getenv("LS_TAGGED_ROWS")) { const int v = atoi(e); if (v >= 0 && v <= LS_ROWS) p.ll_max_rows = v; }
   p.spin_limit = 1 << 22;
   if (const char* e = getenv("LS_SPIN_LIMIT")) { const int v = atoi(e); if (v > 0) p.spin_limit = v; }
-  p.q_pf = c->ws + lay.q_pf; p.o_pf = c->ws + lay.o_pf;
   set_decomposition(c);
   c->host_layers = lw;
   LsPfParams& f = c->pf;
@@ -302,8 +299,6 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   f.o_pf = c->ws + lay.o_pf; f.act_pf = c->ws + lay.act_pf; f.xbuf = p.xbuf; f.ssq = p.ssq;
   c->gemm_prefill = true;
   if (const char* e = getenv("LS_PREFILL")) c->gemm_prefill = !(e[0] == 'r' || e[0] == '0');   // "rows": 16-row passes
-  c->rows_attn = false;
-  if (const char* e = getenv("LS_PREFILL_ATTN")) c->rows_attn = e[0] == 'r';
   *out = c;
   return LS_OK;
 }
@@ -326,13 +321,6 @@ int ls_set_launch(ls_ctx* c, int32_t wg_per_cu) {
   return c->grid;
 }
 
-static int pf_attn_cb(void* vctx, int layer, int pos0, int M, hipStream_t s) {
-  ls_ctx* c = static_cast<ls_ctx*>(vctx);
-  LsKParams p = program(c, LS_PROG_PF_ATTN);
-  p.n_tokens = M; p.pf_layer = layer; p.pf_pos0 = pos0;
-  return launch(c, p, s) == LS_OK ? 0 : 1;
-}
-
 // The prompt pass: GEMM path for prompts of kPrefillMinRows rows or more (in chunks of pf_rows),
 // else the 16-row passes of the decode kernel.  Ends with the decoding state of a finished prefill.
 static int enqueue_prefill(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, int32_t layers_used,
@@ -349,7 +337,7 @@ static int enqueue_prefill(ls_ctx* c, const int32_t* dev_prompt, int32_t n_promp
   int last_rows = 0;
   for (int pos0 = 0; pos0 < n_prompt; pos0 += c->lay.pf_rows) {
     const int M = n_prompt - pos0 < c->lay.pf_rows ? n_prompt - pos0 : c->lay.pf_rows;
-    if (ls_prefill_layers(&f, c->host_layers.data(), pos0, M, s, c->rows_attn ? pf_attn_cb : nullptr, c) != 0) return LS_E_HIP;
+    if (ls_prefill_layers(&f, c->host_layers.data(), pos0, M, s) != 0) return LS_E_HIP;
     last_rows = M;
   }
   if (ls_prefill_finish(&f, last_rows - 1, s) != 0) return LS_E_HIP;

@@ -53,8 +53,7 @@ enum LsProgramKind {
   LS_PROG_DRAFT = 2,
   LS_PROG_VERIFY = 3,
   LS_PROG_GENERATE = 4,  // rounds of draft+verify (d > 0) or single-token passes (d == 0)
-  LS_PROG_PF_ATTN = 5,   // GEMM prefill: attention of rows [pf_pos0, pf_pos0+n_tokens) of layer pf_layer
-  LS_PROG_PF_FINISH = 6  // GEMM prefill: head on residual row 0, then the state of a finished prefill
+  LS_PROG_PF_FINISH = 5  // GEMM prefill: head on residual row 0, then the state of a finished prefill
 };
 
 struct LsKParams {
@@ -97,9 +96,6 @@ struct LsKParams {
   uint64_t *ct;                     // [2][grid][16][4] argmax candidates, two buffers used alternately
   uint32_t *attn_cnt_ll;            // [nkv] monotone completion counters
   int32_t ll_max_rows;
-  // GEMM prefill: q rows / attention output rows of the prompt chunk, and which layer / rows
-  void *q_pf, *o_pf;
-  int32_t pf_layer, pf_pos0;
   // optional timeline of one workgroup: (100 MHz wall clock << 8) | tag, appended per event
   unsigned long long *prof;
   int32_t prof_cap, prof_wg;

@@ -28,7 +28,7 @@ static const void* kernel_for(int kind, int d, int dtype_is_bf16, int hd) {
   const void* k[3];
   if (dtype_is_bf16) { if (hd == 128) ls_variant_kernels_bf16_hd128(k); else ls_variant_kernels_bf16_hd64(k); }
   else { if (hd == 128) ls_variant_kernels_f32_hd128(k); else ls_variant_kernels_f32_hd64(k); }
-  const bool prompt = kind == LS_PROG_PREFILL || kind == LS_PROG_SCORE || kind == LS_PROG_PF_ATTN || kind == LS_PROG_PF_FINISH;
+  const bool prompt = kind == LS_PROG_PREFILL || kind == LS_PROG_SCORE || kind == LS_PROG_PF_FINISH;
   const bool greedy = kind == LS_PROG_GENERATE && d == 0;
   return prompt ? k[0] : (greedy ? k[2] : k[1]);
 }

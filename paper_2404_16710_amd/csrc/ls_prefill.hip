@@ -428,8 +428,7 @@ hipError_t launch_attn(const LsPfParams& p, int layer, int pos0, int M, hipStrea
 }
 
 template <typename T>
-int run_layers(const LsPfParams& p, const LsLayerW* lw, int pos0, int M, hipStream_t s,
-               int (*attn)(void*, int, int, int, hipStream_t), void* attn_ctx) {
+int run_layers(const LsPfParams& p, const LsLayerW* lw, int pos0, int M, hipStream_t s) {
   const int dm = p.dm, qd = p.qd, kvd = p.kvd, ffn = p.ffn;
   pf_embed_kernel<T><<<dim3(M), dim3(256), 0, s>>>(p.tokens + pos0, static_cast<const T*>(p.embed), p.x_pf, dm, p.vocab);
   for (int l = 0; l < p.layers_used; ++l) {
@@ -444,11 +443,7 @@ int run_layers(const LsPfParams& p, const LsLayerW* lw, int pos0, int M, hipStre
     if (launch_gemm<T, EPI_ROPE_K>(g, s) != hipSuccess) return 1;
     g.W = W.wv; g.N = kvd; g.out = p.vcache;
     if (launch_gemm<T, EPI_V>(g, s) != hipSuccess) return 1;
-    if (attn != nullptr) {          // attention through the decode kernel's stage (comparison aid)
-      if (attn(attn_ctx, l, pos0, M, s) != 0) return 1;
-    } else if (launch_attn<T>(p, l, pos0, M, s) != hipSuccess) {
-      return 1;
-    }
+    if (launch_attn<T>(p, l, pos0, M, s) != hipSuccess) return 1;
     g.A = p.o_pf; g.lda = qd; g.K = qd; g.W = W.wo; g.N = dm; g.x = p.x_pf; g.capture = nullptr;
     if (launch_gemm<T, EPI_RESID>(g, s) != hipSuccess) return 1;
     pf_rmsnorm_kernel<T><<<dim3(M), dim3(256), 0, s>>>(p.x_pf, static_cast<const T*>(W.ffn_norm), static_cast<T*>(p.a_pf), dm, p.eps);
@@ -463,13 +458,9 @@ int run_layers(const LsPfParams& p, const LsLayerW* lw, int pos0, int M, hipStre
 
 }  // namespace
 
-// Runs layers 0..layers_used-1 over rows [pos0, pos0+M) of the prompt (M <= pf_rows).  `attn`, when
-// not null, is called once per layer to enqueue the attention of those rows instead of the MFMA
-// attention kernel (q rows in q_pf, output to o_pf).
-extern "C" int ls_prefill_layers(const LsPfParams* p, const LsLayerW* host_layers, int pos0, int M, hipStream_t s,
-                                 int (*attn)(void*, int, int, int, hipStream_t), void* attn_ctx) {
-  return p->is_bf16 ? run_layers<bf16_t>(*p, host_layers, pos0, M, s, attn, attn_ctx)
-                    : run_layers<float>(*p, host_layers, pos0, M, s, attn, attn_ctx);
+// Runs layers 0..layers_used-1 over rows [pos0, pos0+M) of the prompt (M <= pf_rows).
+extern "C" int ls_prefill_layers(const LsPfParams* p, const LsLayerW* host_layers, int pos0, int M, hipStream_t s) {
+  return p->is_bf16 ? run_layers<bf16_t>(*p, host_layers, pos0, M, s) : run_layers<float>(*p, host_layers, pos0, M, s);
 }
 
 extern "C" int ls_prefill_finish(const LsPfParams* p, int last_row, hipStream_t s) {
