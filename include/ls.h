@@ -160,6 +160,12 @@ int ls_debug_timeline(ls_ctx *ctx, unsigned long long *dev_events, int32_t capac
  * byte counters are scaled by.  Enqueue only. */
 int ls_debug_copy(void *dev_dst, const void *dev_src, size_t bytes, void *stream);
 
+/* Debug aid: how many polls a workgroup spends in one wait for the others before it gives up
+ * (0 restores the default of about four million).  When a wait expires every workgroup leaves, the
+ * call that launched the kernel returns LS_E_DEVICE, and the next ls_prefill / ls_generate* / ls_score
+ * starts from rebuilt counters.  A limit of 1 makes that path testable without a hung kernel. */
+int ls_debug_spin_limit(ls_ctx *ctx, int32_t polls);
+
 /* Launch shape: workgroups per compute unit (1 or 2) used by later calls; 0 restores the default.
  * Returns the number of workgroups a launch will use, or a negative error. */
 int ls_set_launch(ls_ctx *ctx, int32_t workgroups_per_cu);

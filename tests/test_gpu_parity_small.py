@@ -276,3 +276,23 @@ def test_argument_errors_leave_no_work():
     pos, last, n_gen = gm.get_state()
     assert n_gen >= 2 and pos == len(prompt) + n_gen - 1
     gm.close()
+
+
+@pytest.mark.parametrize("rows", [0, 16])
+def test_expired_wait_is_reported_and_the_next_prompt_recovers(rows):
+    """Failure handling, forced from the host: with a limit of one poll per wait some workgroup
+    gives up at once, every workgroup then leaves (no kernel hangs or faults), the call reports
+    LS_E_DEVICE, and after the limit is restored the same context generates the right tokens again."""
+    from paper_2404_16710_amd.binding import LsError
+    w = CASES["c1"]
+    ws, prompt, om, gm = _setup(w)
+    gm.set_exchange(rows)
+    want, _ = gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
+    gm.debug_spin_limit(1)
+    with pytest.raises(LsError) as ei:
+        gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
+    assert ei.value.code == -6
+    gm.debug_spin_limit(0)
+    got, st = gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
+    assert got == want and st.generated == w.n_new
+    gm.close()
