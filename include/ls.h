@@ -123,6 +123,15 @@ int ls_generate(ls_ctx *ctx, const int32_t *dev_prompt, int32_t n_prompt, int32_
                 int32_t exit_layer, int32_t d, int32_t eos_id, int32_t *dev_out_tokens,
                 ls_stats *host_stats, void *stream);
 
+/* Ablation of the shared cache and exit states (Section 4.3.3; the cache-reuse table of the
+ * appendix): same arguments, output tokens and statistics as ls_generate with d >= 1, but every
+ * round verifies with ALL layers over its 1+d tokens instead of continuing from the exit-layer
+ * states and early-layer cache the draft stage left (and skips the early-layer pass of the last
+ * draft, which only exists to feed that continuation).  The difference in time is what the reuse saves. */
+int ls_generate_no_reuse(ls_ctx *ctx, const int32_t *dev_prompt, int32_t n_prompt, int32_t max_new,
+                         int32_t exit_layer, int32_t draft_len, int32_t eos_token,
+                         int32_t *dev_out_tokens, ls_stats *host_stats, void *stream);
+
 /* Early exit on its own (Section 4.2): like ls_generate with d = 0, but every pass, the prefill
  * included, runs layers 0..exit_layer-1 only and predicts with g(x_E). */
 int ls_generate_early_exit(ls_ctx *ctx, const int32_t *dev_prompt, int32_t n_prompt,
@@ -135,6 +144,13 @@ int ls_generate_early_exit(ls_ctx *ctx, const int32_t *dev_prompt, int32_t n_pro
  * (DEVICE float[n]).  Overwrites the KV cache and invalidates the decoding state.  Synchronises. */
 int ls_score(ls_ctx *ctx, const int32_t *dev_tokens, int32_t n, int32_t n_layers_used,
              int32_t *dev_argmax, float *dev_margin, void *stream);
+
+/* The unembedding probe of Section 3 (which layer first predicts the final token): like ls_score
+ * over all layers, but the shared head g is applied to the output of EVERY layer.  dev_argmax is
+ * DEVICE int32[n_layers][n], dev_margin DEVICE float[n_layers][n] or NULL; row l holds argmax g(x_{l+1}).
+ * Overwrites the KV cache and invalidates the decoding state.  Synchronises. */
+int ls_probe_layers(ls_ctx *ctx, const int32_t *dev_tokens, int32_t n, int32_t *dev_argmax,
+                    float *dev_margin, void *stream);
 
 /* Inspection: synchronises `stream` and returns the decoding state (HOST out-pointers, any may
  * be NULL).  Returns LS_E_DEVICE if the device flagged an error. */

@@ -95,10 +95,13 @@ def greedy_full(model: OracleModel, prompt, n_new: int, max_seq: Optional[int] =
 
 
 def self_speculative(model: OracleModel, prompt, n_new: int, exit_layer: int, d: int,
-                     max_seq: Optional[int] = None, round_hook=None) -> DecodeResult:
+                     max_seq: Optional[int] = None, round_hook=None, reuse: bool = True) -> DecodeResult:
     """Greedy self-speculative decoding, Section 4.3 / Appendix A.4.
 
     round_hook(cache, pos, out) is called after every round (tests use it to inspect the cache).
+    reuse=False is the ablation of Section 4.3.3 / the cache-reuse table of the appendix: verification
+    does not take the draft stage's exit states and early-layer cache, it runs all L layers over the
+    round's 1+d tokens (and the last draft needs no early-layer pass of its own).
     """
     L, E = model.cfg.n_layers, exit_layer
     assert 1 <= E <= L and d >= 1
@@ -119,12 +122,15 @@ def self_speculative(model: OracleModel, prompt, n_new: int, exit_layer: int, d:
             D.append(argmax_lowest(lg))
             dm_.append(top2_margin(lg))
             u = D[-1]
-        # the last draft has not been an input yet: early layers only, no head
-        x = model.run_layers(model.embed_tokens([D[-1]]), [pos + d], cache, 0, E)
-        X.append(x[0])
-        # self-verification: layers E..L-1 over the 1+d rows in one pass
-        rows = np.stack(X, axis=0)
-        xl = model.run_layers(rows, list(range(pos, pos + d + 1)), cache, E, L)
+        if reuse:
+            # the last draft has not been an input yet: early layers only, no head
+            x = model.run_layers(model.embed_tokens([D[-1]]), [pos + d], cache, 0, E)
+            X.append(x[0])
+            # self-verification: layers E..L-1 over the 1+d rows in one pass
+            rows = np.stack(X, axis=0)
+            xl = model.run_layers(rows, list(range(pos, pos + d + 1)), cache, E, L)
+        else:
+            xl = model.run_layers(model.embed_tokens([last] + D), list(range(pos, pos + d + 1)), cache, 0, L)
         lg = model.head(xl)
         V = [argmax_lowest(lg[i]) for i in range(d + 1)]
         vm = [top2_margin(lg[i]) for i in range(d + 1)]
@@ -161,3 +167,18 @@ def early_exit_greedy(model: OracleModel, prompt, n_new: int, exit_layer: int) -
         tokens.append(argmax_lowest(logits))
         margins.append(top2_margin(logits))
     return DecodeResult(tokens, margins)
+
+
+def layer_probe(model: OracleModel, tokens):
+    """The unembedding probe of Section 3: the shared head applied to the output of every layer.
+    Returns (ids, margins), each [L][n]: ids[l][i] = argmax g(x_{l+1}) at row i of the causal sequence."""
+    n = len(tokens)
+    cache = model.new_cache(n + 1)
+    hidden = []
+    model.run_layers(model.embed_tokens(list(tokens)), list(range(n)), cache, 0, model.cfg.n_layers, hidden)
+    ids, margins = [], []
+    for x in hidden:
+        lg = model.head(x)
+        ids.append([argmax_lowest(lg[i]) for i in range(n)])
+        margins.append([top2_margin(lg[i]) for i in range(n)])
+    return ids, margins

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = (
     "ls_workspace_bytes", "ls_load_weights", "ls_prefill", "ls_draft", "ls_verify", "ls_generate",
-    "ls_generate_early_exit", "ls_score", "ls_get_state", "ls_peek_round", "ls_debug_capture",
+    "ls_generate_no_reuse", "ls_generate_early_exit", "ls_score", "ls_probe_layers", "ls_get_state", "ls_peek_round", "ls_debug_capture",
     "ls_debug_timeline", "ls_debug_copy", "ls_set_launch", "ls_set_exchange", "ls_debug_spin_limit", "ls_strerror", "ls_destroy",
 )
 
@@ -92,8 +92,12 @@ def lib() -> C.CDLL:
     L.ls_verify.argtypes = [vp, i32, i32, vp]
     L.ls_generate.restype = C.c_int
     L.ls_generate.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, C.POINTER(ls_stats), vp]
+    L.ls_generate_no_reuse.restype = C.c_int
+    L.ls_generate_no_reuse.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, C.POINTER(ls_stats), vp]
     L.ls_generate_early_exit.restype = C.c_int
     L.ls_generate_early_exit.argtypes = [vp, vp, i32, i32, i32, vp, C.POINTER(ls_stats), vp]
+    L.ls_probe_layers.restype = C.c_int
+    L.ls_probe_layers.argtypes = [vp, vp, i32, vp, vp, vp]
     L.ls_score.restype = C.c_int
     L.ls_score.argtypes = [vp, vp, i32, i32, vp, vp, vp]
     L.ls_get_state.restype = C.c_int
@@ -235,6 +239,16 @@ class LsModel:
         stats = Stats(st.rounds, st.drafted, st.accepted, st.generated, st.ms_prefill, st.ms_decode)
         return out.cpu().numpy()[: stats.generated].tolist(), stats
 
+    def generate_no_reuse(self, prompt: Sequence[int], max_new: int, exit_layer: int, d: int, eos_id: int = -1):
+        p = self._dev_i32(prompt)
+        out = self.torch.empty(max_new, dtype=self.torch.int32, device=self.device)
+        st = ls_stats()
+        _check(self.lib.ls_generate_no_reuse(self.ctx, C.c_void_p(p.data_ptr()), len(prompt), max_new, exit_layer, d,
+                                             eos_id, C.c_void_p(out.data_ptr()), C.byref(st), self._stream()),
+               "ls_generate_no_reuse")
+        stats = Stats(st.rounds, st.drafted, st.accepted, st.generated, st.ms_prefill, st.ms_decode)
+        return out.cpu().numpy()[: stats.generated].tolist(), stats
+
     def generate_early_exit(self, prompt: Sequence[int], max_new: int, exit_layer: int):
         p = self._dev_i32(prompt)
         out = self.torch.empty(max_new, dtype=self.torch.int32, device=self.device)
@@ -252,6 +266,16 @@ class LsModel:
         mg = self.torch.empty(n, dtype=self.torch.float32, device=self.device)
         _check(self.lib.ls_score(self.ctx, C.c_void_p(t.data_ptr()), n, n_layers_used or self.cfg.n_layers,
                                  C.c_void_p(am.data_ptr()), C.c_void_p(mg.data_ptr()), self._stream()), "ls_score")
+        return am.cpu().numpy(), mg.cpu().numpy()
+
+    def probe_layers(self, tokens: Sequence[int]):
+        """argmax and margin of g(x_l) for every layer l = 1..L and every row: arrays [L][n]."""
+        t = self._dev_i32(tokens)
+        n, L = len(tokens), self.cfg.n_layers
+        am = self.torch.empty((L, n), dtype=self.torch.int32, device=self.device)
+        mg = self.torch.empty((L, n), dtype=self.torch.float32, device=self.device)
+        _check(self.lib.ls_probe_layers(self.ctx, C.c_void_p(t.data_ptr()), n, C.c_void_p(am.data_ptr()),
+                                        C.c_void_p(mg.data_ptr()), self._stream()), "ls_probe_layers")
         return am.cpu().numpy(), mg.cpu().numpy()
 
     def get_state(self):

@@ -395,7 +395,8 @@ int ls_verify(ls_ctx* c, int32_t E, int32_t d, void* stream) {
 }
 
 static int generate_impl(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, int32_t max_new, int32_t E, int32_t d,
-                         int32_t eos, int32_t layers_used, int32_t* dev_out, ls_stats* stats, void* stream) {
+                         int32_t eos, int32_t layers_used, int32_t* dev_out, ls_stats* stats, void* stream,
+                         bool no_reuse = false) {
   if (!c || !dev_prompt || !dev_out) return LS_E_ARG;
   if (n_prompt < 1 || max_new < 1) return LS_E_RANGE;
   if (d < 0 || d > c->cfg.max_draft) return LS_E_RANGE;
@@ -412,6 +413,7 @@ static int generate_impl(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt,
   if (hipEventRecord(c->ev[1], s) != hipSuccess) return LS_E_HIP;
   LsKParams g = program(c, LS_PROG_GENERATE);
   g.E = E; g.d = d; g.max_new = max_new; g.eos = eos; g.out_tokens = dev_out; g.layers_used = layers_used;
+  g.no_reuse = no_reuse ? 1 : 0;
   rc = launch(c, g, s);
   if (rc != LS_OK) return rc;
   if (hipEventRecord(c->ev[2], s) != hipSuccess) return LS_E_HIP;
@@ -434,6 +436,13 @@ int ls_generate(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, int32_t 
   return generate_impl(c, dev_prompt, n_prompt, max_new, E, d, eos, c->cfg.n_layers, dev_out, stats, stream);
 }
 
+int ls_generate_no_reuse(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, int32_t max_new, int32_t E, int32_t d,
+                         int32_t eos, int32_t* dev_out, ls_stats* stats, void* stream) {
+  if (!c) return LS_E_ARG;
+  if (d < 1) return LS_E_RANGE;
+  return generate_impl(c, dev_prompt, n_prompt, max_new, E, d, eos, c->cfg.n_layers, dev_out, stats, stream, true);
+}
+
 int ls_generate_early_exit(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, int32_t max_new, int32_t E,
                            int32_t* dev_out, ls_stats* stats, void* stream) {
   if (!c) return LS_E_ARG;
@@ -441,13 +450,14 @@ int ls_generate_early_exit(ls_ctx* c, const int32_t* dev_prompt, int32_t n_promp
   return generate_impl(c, dev_prompt, n_prompt, max_new, E, 0, -1, E, dev_out, stats, stream);
 }
 
-int ls_score(ls_ctx* c, const int32_t* dev_tokens, int32_t n, int32_t layers_used, int32_t* dev_argmax,
-             float* dev_margin, void* stream) {
+static int score_impl(ls_ctx* c, const int32_t* dev_tokens, int32_t n, int32_t layers_used, int32_t* dev_argmax,
+                      float* dev_margin, void* stream, bool probe) {
   if (!c || !dev_tokens || !dev_argmax) return LS_E_ARG;
   if (n < 1 || layers_used < 1 || layers_used > c->cfg.n_layers) return LS_E_RANGE;
   if (n > c->cfg.max_seq) return LS_E_CAPACITY;
   hipStream_t s = static_cast<hipStream_t>(stream);
   LsKParams p = program(c, LS_PROG_SCORE);
+  p.probe = probe ? 1 : 0;
   p.tokens = dev_tokens; p.n_tokens = n; p.layers_used = layers_used; p.out_tokens = dev_argmax; p.out_margin = dev_margin;
   int rc = launch(c, p, s);
   if (rc != LS_OK) return rc;
@@ -456,6 +466,17 @@ int ls_score(ls_ctx* c, const int32_t* dev_tokens, int32_t n, int32_t layers_use
   rc = read_state(c, &st, s);
   if (rc != LS_OK) return rc;
   return st.error ? LS_E_DEVICE : LS_OK;
+}
+
+int ls_score(ls_ctx* c, const int32_t* dev_tokens, int32_t n, int32_t layers_used, int32_t* dev_argmax,
+             float* dev_margin, void* stream) {
+  return score_impl(c, dev_tokens, n, layers_used, dev_argmax, dev_margin, stream, false);
+}
+
+int ls_probe_layers(ls_ctx* c, const int32_t* dev_tokens, int32_t n, int32_t* dev_argmax, float* dev_margin,
+                    void* stream) {
+  if (!c) return LS_E_ARG;
+  return score_impl(c, dev_tokens, n, c->cfg.n_layers, dev_argmax, dev_margin, stream, true);
 }
 
 int ls_get_state(ls_ctx* c, int32_t* pos, int32_t* last, int32_t* n_gen, void* stream) {

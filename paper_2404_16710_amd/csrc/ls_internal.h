@@ -82,6 +82,8 @@ struct LsKParams {
   int32_t gs_x, gs_ffn, ssq_nt;
   // program
   int32_t kind, E, d, max_new, eos, n_tokens, layers_used;
+  int32_t probe;      // LS_PROG_SCORE: argmax of the head after every layer, outputs [layer][row]
+  int32_t no_reuse;   // rounds verify with all L layers instead of continuing from the exit states (ablation)
   const int32_t *tokens;
   int32_t *out_tokens;
   float *out_margin;

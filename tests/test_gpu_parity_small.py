@@ -296,3 +296,42 @@ def test_expired_wait_is_reported_and_the_next_prompt_recovers(rows):
     got, st = gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
     assert got == want and st.generated == w.n_new
     gm.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "gqa-hd128-bf16", "gqa2-f32"])
+def test_generation_without_cache_reuse_matches(name):
+    """ls_generate_no_reuse (ablation of Section 4.3.3): verification recomputes the early layers of the
+    round's rows.  The rows of a pass do not influence each other's arithmetic, so tokens and round
+    statistics are those of ls_generate exactly; against the oracle's own no-reuse loop up to near-ties."""
+    w = CASES[name]
+    ws, prompt, om, gm = _setup(w)
+    toks, st = gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
+    got, sn = gm.generate_no_reuse(prompt, w.n_new, w.exit_layer, w.draft_len)
+    assert got == toks
+    assert (sn.rounds, sn.drafted, sn.accepted, sn.generated) == (st.rounds, st.drafted, st.accepted, st.generated)
+    ref = O.self_speculative(om, prompt, w.n_new, w.exit_layer, w.draft_len, reuse=False)
+    same_until_near_tie(got, ref.tokens, ref.margins)
+    gm.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "c1-bf16", "gqa2-f32"])
+def test_layer_probe_matches_oracle(name):
+    """ls_probe_layers: argmax of g(x_l) after every layer for every row of a 40-token sequence (two
+    full 16-row passes and a ragged one), against the oracle's probe; near-ties excluded."""
+    w = CASES[name]
+    ws, prompt, om, gm = _setup(w)
+    seq = (list(prompt) * 2)[:40]
+    am, mg = gm.probe_layers(seq)
+    ids, margins = O.layer_probe(om, seq)
+    L = w.model.n_layers
+    assert am.shape == (L, len(seq))
+    firm = 0
+    for l in range(L):
+        for i in range(len(seq)):
+            if margins[l][i] >= NEAR_TIE:
+                firm += 1
+                assert am[l][i] == ids[l][i], (l, i, margins[l][i], mg[l][i])
+    assert firm > L * len(seq) // 2
+    full, _ = gm.score(seq)
+    assert list(am[L - 1]) == list(full)          # the last layer's probe is the full model, bit for bit
+    gm.close()

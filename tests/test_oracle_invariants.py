@@ -38,6 +38,35 @@ def test_self_speculative_equals_full_greedy(c1, E, d):
         assert r.n_accept == d or r.draft[r.n_accept] != r.verify[r.n_accept]
 
 
+@pytest.mark.parametrize("E,d", [(2, 4), (1, 3), (3, 6)])
+def test_verifying_without_cache_reuse_changes_nothing_but_the_work(c1, E, d):
+    """Section 4.3.3: reusing the draft stage's cache and exit states is an optimisation only; verifying
+    with all L layers over the round's tokens gives the same rounds, drafts and verified tokens."""
+    w, m, p = _model(c1)
+    a = O.self_speculative(m, p, w.n_new, E, d)
+    b = O.self_speculative(m, p, w.n_new, E, d, reuse=False)
+    assert b.tokens == a.tokens == O.greedy_full(m, p, w.n_new).tokens
+    assert [(r.pos, r.draft, r.verify, r.n_accept) for r in b.rounds] == [(r.pos, r.draft, r.verify, r.n_accept) for r in a.rounds]
+
+
+def test_layer_probe_agrees_with_brute_force_and_with_early_exit(c1):
+    """The per-layer probe (Section 3) is the head applied to x_1..x_L: row by row it must equal the
+    argmax of g over the states of the cache-free recomputation, its last layer is the full model, and
+    its layer E at the last prompt row is the first token of early-exit generation (Section 4.2)."""
+    w, m, p = _model(c1)
+    seq = list(p) + O.greedy_full(m, p, 6).tokens[:5]
+    ids, margins = O.layer_probe(m, seq)
+    hidden, logits = O.forward_nocache(m, seq)
+    L = w.model.n_layers
+    for l in range(L):
+        lg = m.head(hidden[l + 1])
+        assert ids[l] == [O.argmax_lowest(lg[i]) for i in range(len(seq))]
+    assert ids[L - 1] == [O.argmax_lowest(logits[i]) for i in range(len(seq))]
+    assert all(g >= 0 for row in margins for g in row)
+    for E in (1, 2, 3):
+        assert ids[E - 1][len(p) - 1] == O.early_exit_greedy(m, p, 1, E).tokens[0]
+
+
 def test_float32_oracle_is_lossless_too(c1):
     w, m, p = _model(c1, np.float32)
     g = O.greedy_full(m, p, w.n_new)
