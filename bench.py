@@ -110,6 +110,13 @@ def main() -> int:
     ar_ms_dec = float(np.mean([r[1].ms_decode for r in ar_runs]))
     ar_ms_pre = float(np.mean([r[1].ms_prefill for r in ar_runs]))
 
+    # the two other curves of the paper's tables on the same weights: verification without reuse of the
+    # draft stage's cache and exit states (its ablation), and early exit on its own (lossy: other tokens)
+    model.generate_no_reuse(prompt, w.n_new, E, d)
+    nr_toks, nr = model.generate_no_reuse(prompt, w.n_new, E, d)
+    model.generate_early_exit(prompt, w.n_new, E)
+    _, ee = model.generate_early_exit(prompt, w.n_new, E)
+
     b_ss = decode_bytes_selfspec(m, w.n_prompt, E, d, st.rounds, pos_final)
     b_ar = decode_bytes_ar(m, w.n_prompt, w.n_new)
     ach = b_ss / (ms_dec * 1e-3) / 1e9
@@ -139,6 +146,11 @@ def main() -> int:
                         "decode_tokens_per_s": round((w.n_new - 1) / (ar_ms_dec * 1e-3), 2),
                         "ms_prefill": round(ar_ms_pre, 3), "ms_decode": round(ar_ms_dec, 3),
                         "hbm_gbs": round(ach_ar, 1), "hbm_frac": round(ach_ar / HBM_PEAK_GBS, 4)},
+        "no_cache_reuse": {"decode_tokens_per_s": round((w.n_new - 1) / (nr.ms_decode * 1e-3), 2),
+                           "ms_decode": round(nr.ms_decode, 3), "same_ids": bool(nr_toks == toks),
+                           "reuse_saves_ms_per_token": round((nr.ms_decode - ms_dec) / (w.n_new - 1), 4)},
+        "early_exit_only": {"decode_tokens_per_s": round((w.n_new - 1) / (ee.ms_decode * 1e-3), 2),
+                            "ms_decode": round(ee.ms_decode, 3), "exit_layer": E},
         "speedup_vs_full_greedy": round(ar_ms_dec / ms_dec, 3),
         "same_ids_as_full_greedy": bool(toks == ar_toks),
         "roofline": {"bound": "hbm", "kernel": "ls_decode_kernel<bf16> (one launch = all draft + tail + verify passes of a job)",
