@@ -125,7 +125,7 @@ def main() -> int:
     # HBM bytes per decode launch from the committed counter profile of this very workload
     # (FETCH_SIZE + WRITE_SIZE scaled by the copy-kernel reference); null for other workloads
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "decode_kernel_c2_hbm_traffic.md")
+    tpath = os.path.join(ROOT, "profiles", "decode_kernel_c2_hbm_traffic.txt")
     if a.config == "c2" and E == w.exit_layer and d == w.draft_len and os.path.exists(tpath):
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch:"):
