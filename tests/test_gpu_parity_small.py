@@ -172,7 +172,8 @@ def test_large_cache_capacity_groups_attention_tiles(max_seq):
     gm.close()
 
 
-@pytest.mark.parametrize("name,n_prompt", [("c1", 150), ("c1-bf16", 131), ("gqa-hd128-bf16", 257), ("gqa2-f32", 64)])
+@pytest.mark.parametrize("name,n_prompt", [("c1", 150), ("c1-bf16", 131), ("gqa-hd128-bf16", 257), ("gqa2-f32", 64),
+                                           ("c1", 2100), ("gqa-hd128-bf16", 2085)])   # the last two: more than one chunk of 2048 prompt rows
 def test_prefill_hidden_states_and_cache(name, n_prompt):
     """ls_prefill (the GEMM prompt pass for these lengths): per-layer hidden states of every prompt
     row, the first token, and - through one draft/verify round on top of it - the KV cache."""
