@@ -117,6 +117,39 @@ def main() -> int:
     model.generate_early_exit(prompt, w.n_new, E)
     _, ee = model.generate_early_exit(prompt, w.n_new, E)
 
+    # the stages on their own, through the step-by-step calls (one launch each, timed with events on
+    # the launch stream): ls_draft = d draft steps + the early-layer pass of the last draft, ls_verify =
+    # the (d+1)-row pass over layers [E, L) + head + acceptance; a draft step alone = an early-exit token
+    Wl, Wh, kvb = m.layer_weight_bytes(), m.head_weight_bytes(), m.kv_bytes_per_pos_layer()
+    model.prefill(prompt)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    t_draft, t_verify, b_draft, b_verify = [], [], [], []
+    for _ in range(8):
+        pos_r, _, _ = model.get_state()
+        ev[0].record(); model.draft(E, d); ev[1].record(); model.verify(E, d); ev[2].record()
+        torch.cuda.synchronize()
+        t_draft.append(ev[0].elapsed_time(ev[1])); t_verify.append(ev[1].elapsed_time(ev[2]))
+        b_draft.append(sum(E * Wl + Wh + E * (pos_r + i + 1) * kvb for i in range(d)) + E * Wl + E * (pos_r + d + 1) * kvb)
+        b_verify.append((m.n_layers - E) * (Wl + (pos_r + d + 1) * kvb) + Wh)
+    t_draft, t_verify = t_draft[1:], t_verify[1:]            # the first round warms the caches
+    b_draft, b_verify = b_draft[1:], b_verify[1:]
+    gb = lambda by, ms_: float(np.sum(by) / (np.sum(ms_) * 1e-3) / 1e9)
+    ee_bytes = sum(E * Wl + Wh + E * (w.n_prompt + k) * kvb for k in range(1, w.n_new))
+    # streaming reference: the library's plain copy kernel over 1 GiB (read + write)
+    import ctypes
+    c_src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0")
+    c_dst = torch.empty_like(c_src)
+    copy = lambda: model.lib.ls_debug_copy(ctypes.c_void_p(c_dst.data_ptr()), ctypes.c_void_p(c_src.data_ptr()),
+                                           1 << 30, model._stream())
+    copy()
+    ev[0].record()
+    for _ in range(4):
+        copy()
+    ev[1].record()
+    torch.cuda.synchronize()
+    stream_gbs = 4 * 2 * (1 << 30) / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+    del c_src, c_dst
+
     b_ss = decode_bytes_selfspec(m, w.n_prompt, E, d, st.rounds, pos_final)
     b_ar = decode_bytes_ar(m, w.n_prompt, w.n_new)
     ach = b_ss / (ms_dec * 1e-3) / 1e9
@@ -151,11 +184,21 @@ def main() -> int:
                            "reuse_saves_ms_per_token": round((nr.ms_decode - ms_dec) / (w.n_new - 1), 4)},
         "early_exit_only": {"decode_tokens_per_s": round((w.n_new - 1) / (ee.ms_decode * 1e-3), 2),
                             "ms_decode": round(ee.ms_decode, 3), "exit_layer": E},
+        "stages": {"draft_launch": {"ms": round(float(np.mean(t_draft)), 3), "hbm_gbs": round(gb(b_draft, t_draft), 1),
+                                    "hbm_frac": round(gb(b_draft, t_draft) / HBM_PEAK_GBS, 4),
+                                    "what": f"{d} draft steps + early layers of the last draft (ls_draft)"},
+                   "verify_launch": {"ms": round(float(np.mean(t_verify)), 3), "hbm_gbs": round(gb(b_verify, t_verify), 1),
+                                     "hbm_frac": round(gb(b_verify, t_verify) / HBM_PEAK_GBS, 4),
+                                     "what": f"{d + 1} rows through layers [{E}, {m.n_layers}) + head (ls_verify)"},
+                   "draft_step": {"hbm_gbs": round(ee_bytes / (ee.ms_decode * 1e-3) / 1e9, 1),
+                                  "hbm_frac": round(ee_bytes / (ee.ms_decode * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                  "what": f"layers [0, {E}) + head per token (the early-exit job)"}},
         "speedup_vs_full_greedy": round(ar_ms_dec / ms_dec, 3),
         "same_ids_as_full_greedy": bool(toks == ar_toks),
         "roofline": {"bound": "hbm", "kernel": "ls_decode_kernel<bf16> (one launch = all draft + tail + verify passes of a job)",
                      "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "stream_copy_gbs": round(stream_gbs, 1), "frac_of_stream_copy": round(ach / stream_gbs, 4),
                      "bytes_per_launch": int(b_ss), "ms_per_launch": round(ms_dec, 3)},
     }
 
@@ -176,11 +219,15 @@ def main() -> int:
         c0 = time.perf_counter()
         ref = O.self_speculative(om, prompt, n_s, E, d)
         c_all = time.perf_counter() - c0
+        c0 = time.perf_counter()
+        O.greedy_full(om, prompt, max(2, n_s // 2))
+        c_ar = time.perf_counter() - c0
         out["cpu_baseline"] = {
             "value": round(n_s / c_all, 3), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"same weights and {w.n_prompt}-id prompt, first {n_s} of {w.n_new} new tokens "
                       f"(prefill included, {c_pre:.1f}s of {c_all:.1f}s), E={E} d={d}, numpy float32",
             "decode_tokens_per_s": round((n_s - 1) / max(c_all - c_pre, 1e-9), 3),
+            "full_greedy_decode_tokens_per_s": round((max(2, n_s // 2) - 1) / max(c_ar - c_pre, 1e-9), 3),
             "acceptance": round(ref.acceptance, 4),
             "ids_match_gpu_until_near_tie": int(next((i for i, (x, y) in enumerate(zip(toks, ref.tokens)) if x != y), n_s)),
         }
