@@ -24,13 +24,26 @@ extern "C" int ls_launch_copy(const void* src, void* dst, size_t bytes, hipStrea
   return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
-static const void* kernel_for(int kind, int d, int dtype_is_bf16, int hd) {
-  const void* k[3];
+enum { LS_K_PROMPT = 0, LS_K_DECODE, LS_K_GREEDY, LS_K_STEP, LS_K_AUX, LS_K_COUNT };
+
+static const void* kernel_symbol(int which, int dtype_is_bf16, int hd) {
+  const void* k[LS_K_COUNT];
   if (dtype_is_bf16) { if (hd == 128) ls_variant_kernels_bf16_hd128(k); else ls_variant_kernels_bf16_hd64(k); }
   else { if (hd == 128) ls_variant_kernels_f32_hd128(k); else ls_variant_kernels_f32_hd64(k); }
-  const bool prompt = kind == LS_PROG_PREFILL || kind == LS_PROG_SCORE || kind == LS_PROG_PF_FINISH;
-  const bool greedy = kind == LS_PROG_GENERATE && d == 0;
-  return prompt ? k[0] : (greedy ? k[2] : k[1]);
+  return k[which];
+}
+
+// Which of the five names a launch runs under (they share one body): whole self-speculative jobs,
+// whole full-model greedy jobs, single draft / verify launches, and the ablation and early-exit
+// jobs are kept apart so that per-name statistics of a kernel trace are of one kind of work each.
+static int kernel_index(const LsKParams* p) {
+  switch (p->kind) {
+    case LS_PROG_PREFILL: case LS_PROG_SCORE: case LS_PROG_PF_FINISH: return LS_K_PROMPT;
+    case LS_PROG_DRAFT: case LS_PROG_VERIFY: return LS_K_STEP;
+    default: break;
+  }
+  if (p->d == 0) return p->layers_used == p->L ? LS_K_GREEDY : LS_K_AUX;
+  return p->no_reuse ? LS_K_AUX : LS_K_DECODE;
 }
 
 extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid, hipStream_t stream) {
@@ -39,7 +52,7 @@ extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid
   // so an ordinary launch is used; LS_COOPERATIVE_LAUNCH=1 asks the runtime to guarantee residency.
   static const bool coop = []() { const char* v = getenv("LS_COOPERATIVE_LAUNCH"); return v != nullptr && v[0] == '1'; }();
   const size_t smem = LS_SMEM_BYTES + (p->prof != nullptr ? LS_PROF_EVENTS * 8 : 0);
-  const void* fn = kernel_for(p->kind, p->d, dtype_is_bf16, p->hd);
+  const void* fn = kernel_symbol(kernel_index(p), dtype_is_bf16, p->hd);
   hipError_t e = coop ? hipLaunchCooperativeKernel(fn, dim3(grid), dim3(LS_THREADS), args, smem, stream)
                       : hipLaunchKernel(fn, dim3(grid), dim3(LS_THREADS), args, smem, stream);
   return e == hipSuccess ? 0 : (int)e;
@@ -47,8 +60,8 @@ extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid
 
 extern "C" int ls_kernel_setup(int dtype_is_bf16, int hd, int* max_blocks_per_cu) {
   int nb_min = 1 << 30;
-  for (int v = 0; v < 3; ++v) {
-    const void* fn = kernel_for(v == 0 ? (int)LS_PROG_PREFILL : (int)LS_PROG_GENERATE, v == 1 ? 0 : 1, dtype_is_bf16, hd);
+  for (int v = 0; v < LS_K_COUNT; ++v) {
+    const void* fn = kernel_symbol(v, dtype_is_bf16, hd);
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LS_SMEM_BYTES + LS_PROF_EVENTS * 8);
     if (e != hipSuccess) return (int)e;
     int nb = 0;
