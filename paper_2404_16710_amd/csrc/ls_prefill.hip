@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
+#include <stdlib.h>
 
 #include "ls_internal.h"
 
@@ -225,8 +226,192 @@ __global__ __launch_bounds__(256) void pf_gemm_kernel(const PfGemm g) {
   }
 }
 
+// The same product for few rows: 32 x 128 output tiles, so that a prompt of a few hundred rows
+// still gives every compute unit a tile, with the four waves splitting K (each wave takes one
+// 64-byte sub-step of a 256-byte step and keeps a partial 32 x 128 tile, i.e. the same operand
+// reuse per wave as above); the partial tiles are added through LDS in a fixed order and the
+// epilogue then walks the tile row by row, which also makes its stores contiguous.
+constexpr int SBM = 32;
+constexpr int SROWB = 256;
+constexpr int SROWP = SROWB + 16;
+constexpr int SREDP = BN + 4;      // padded fp32 row of the reduction buffer
+
+template <int NW>
+constexpr int ks_smem_bytes() {
+  return (SBM * SROWP + NW * BN * SROWP) > (2 * NW * SBM * SREDP * 4) ? (SBM * SROWP + NW * BN * SROWP)
+                                                                     : (2 * NW * SBM * SREDP * 4);
+}
+
+template <typename T, int EPI>
+__global__ __launch_bounds__(256) void pf_gemm_ks_kernel(const PfGemm g) {
+  constexpr int EPV = PT<T>::EPV;
+  constexpr int BK = SROWB / (int)sizeof(T);
+  constexpr int NW = (EPI == EPI_GU) ? 2 : 1;
+  extern __shared__ __align__(16) char ks_smem[];
+  char* As = ks_smem;
+  char* Ws = ks_smem + SBM * SROWP;   // [NW][BN][SROWP]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, gq = lane >> 4;
+  const int n0 = blockIdx.x * BN, m0 = blockIdx.y * SBM;
+  const T* Ag = static_cast<const T*>(g.A);
+  const T* Wg[2] = {static_cast<const T*>(g.W), static_cast<const T*>(g.W2)};
+
+  f32x4 acc[NW][2][8];
+#pragma unroll
+  for (int w = 0; w < NW; ++w)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[w][i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  uint4 ra[2], rw[NW][8];
+  auto gload = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int unit = tid + 256 * i, row = unit >> 4, u = unit & 15;
+      const int k = k0 + u * EPV, ma = m0 + row;
+      const bool aok = k < g.K && ma < g.M;
+      const uint4 va = *reinterpret_cast<const uint4*>(Ag + (size_t)(aok ? ma : 0) * g.lda + (aok ? k : 0));
+      ra[i] = aok ? va : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int unit = tid + 256 * i, row = unit >> 4, u = unit & 15;
+      const int k = k0 + u * EPV, na = n0 + row;
+      const bool wok = k < g.K && na < g.N;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const uint4 vw = *reinterpret_cast<const uint4*>(Wg[w] + (size_t)(wok ? na : 0) * g.K + (wok ? k : 0));
+        rw[w][i] = wok ? vw : make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+  auto lstore = [&]() {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int unit = tid + 256 * i, row = unit >> 4, u = unit & 15;
+      *reinterpret_cast<uint4*>(As + row * SROWP + u * 16) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int unit = tid + 256 * i, row = unit >> 4, u = unit & 15;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) *reinterpret_cast<uint4*>(Ws + (w * BN + row) * SROWP + u * 16) = rw[w][i];
+    }
+  };
+
+  gload(0);
+  for (int k0 = 0; k0 < g.K; k0 += BK) {
+    __syncthreads();
+    lstore();
+    __syncthreads();
+    if (k0 + BK < g.K) gload(k0 + BK);
+    uint4 fa[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      fa[i] = *reinterpret_cast<const uint4*>(As + (i * 16 + r) * SROWP + (wave * 4 + gq) * 16);
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint4 fb = *reinterpret_cast<const uint4*>(Ws + (w * BN + j * 16 + r) * SROWP + (wave * 4 + gq) * 16);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) PT<T>::mma(acc[w][i][j], fa[i], fb);
+      }
+    }
+  }
+
+  // waves 0 and 1 store their partial tiles, waves 2 and 3 add theirs on top (each lane to the
+  // addresses of the same tile elements), the epilogue adds the two buffers: ((w0 + w2) + (w1 + w3))
+  float* red = reinterpret_cast<float*>(ks_smem);   // [2][NW][SBM][SREDP]
+  __syncthreads();
+#pragma unroll
+  for (int phase = 0; phase < 2; ++phase) {
+    if ((wave >> 1) == phase) {
+      float* rb = red + (size_t)(wave & 1) * NW * SBM * SREDP;
+#pragma unroll
+      for (int w = 0; w < NW; ++w)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+              float* dst = rb + ((size_t)w * SBM + i * 16 + 4 * gq + jj) * SREDP + 16 * j + r;
+              if (phase == 0) *dst = acc[w][i][j][jj];
+              else *dst += acc[w][i][j][jj];
+            }
+    }
+    __syncthreads();
+  }
+
+  const int half = g.hd / 2;
+  const float* r0 = red;
+  const float* r1 = red + (size_t)NW * SBM * SREDP;
+  auto val = [&](int w, int ml, int nl) {
+    const size_t o = ((size_t)w * SBM + ml) * SREDP + nl;
+    return r0[o] + r1[o];
+  };
+  for (int e = tid; e < SBM * BN; e += 256) {
+    const int ml = e / BN, nl = e - ml * BN;
+    const int m = m0 + ml, n = n0 + nl;
+    if (m >= g.M || n >= g.N) continue;
+    const int pos = g.pos0 + m;
+    const float v = val(0, ml, nl);
+    if (EPI == EPI_RESID) {
+      float* xr = g.x + (size_t)m * g.N + n;
+      const float nv = *xr + v;
+      *xr = nv;
+      if (g.capture != nullptr) g.capture[(size_t)pos * g.N + n] = nv;
+    } else if (EPI == EPI_GU) {
+      const float up = val(NW - 1, ml, nl);
+      PT<T>::st(static_cast<T*>(g.out) + (size_t)m * g.ldo + n, (v / (1.0f + expf(-v))) * up);
+    } else if (EPI == EPI_V) {
+      const int h = n / g.hd, d = n - h * g.hd;
+      PT<T>::st(static_cast<T*>(g.out) + (((size_t)g.layer * g.nkv + h) * g.max_seq + pos) * g.hd + d, v);
+    } else {
+      // rotation mixes columns d and d + hd/2 of one head; a 128-column tile holds whole heads
+      const int h = n / g.hd, d = n - h * g.hd;
+      if (d < half) {
+        const float b = val(0, ml, nl + half);
+        const float c = g.rope_cos[(size_t)pos * half + d], sn = g.rope_sin[(size_t)pos * half + d];
+        const float lo = v * c - b * sn, hi = b * c + v * sn;
+        T* dst = (EPI == EPI_ROPE_Q) ? static_cast<T*>(g.out) + (size_t)m * g.ldo + h * g.hd
+                                     : static_cast<T*>(g.out) + (((size_t)g.layer * g.nkv + h) * g.max_seq + pos) * g.hd;
+        PT<T>::st(dst + d, lo);
+        PT<T>::st(dst + d + half, hi);
+      }
+    }
+  }
+}
+
+// Few 128 x 128 tiles (a short prompt) leave most compute units without work: then 32-row tiles.
+// Both kernels are bound by how fast a compute unit takes in its operand tiles (one K step in
+// flight per workgroup), so the small tile's lower reuse only pays below about half a tile per
+// compute unit (measured on 256 CUs: 64 tiles 1.8x faster, 176 tiles 1.5x slower).
+static bool use_small_tiles(const PfGemm& g) {
+  static const int forced = []() { const char* v = getenv("LS_PF_SMALL_TILES"); return v ? atoi(v) : -1; }();   // tuning aid
+  if (forced >= 0) return forced != 0;
+  const long tiles = (long)((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM);
+  return tiles < 128;
+}
+
 template <typename T, int EPI>
 hipError_t launch_gemm(const PfGemm& g, hipStream_t s) {
+  if (use_small_tiles(g)) {
+    constexpr int NW = (EPI == EPI_GU) ? 2 : 1;
+    constexpr int smem = ks_smem_bytes<NW>();
+    static bool configured = false;   // (per instantiation; the attribute is per function, not per device state that could go stale)
+    if (!configured) {
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_ks_kernel<T, EPI>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+      if (e != hipSuccess) return e;
+      configured = true;
+    }
+    dim3 grid((g.N + BN - 1) / BN, (g.M + SBM - 1) / SBM);
+    pf_gemm_ks_kernel<T, EPI><<<grid, dim3(256), smem, s>>>(g);
+    return hipGetLastError();
+  }
   dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM);
   pf_gemm_kernel<T, EPI><<<grid, dim3(256), 0, s>>>(g);
   return hipGetLastError();

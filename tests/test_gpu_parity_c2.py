@@ -82,6 +82,7 @@ def test_c2_round_replay(c2):
     w, prompt, om, gm, ref = c2
     E, d = w.exit_layer, w.draft_len
     checked = 0
+    gpu_side_ties = 0
     for r in ref.rounds[:3] + ref.rounds[-2:]:
         seq = list(prompt) + ref.tokens[: r.pos - len(prompt)]
         gm.prefill(seq)
@@ -91,8 +92,16 @@ def test_c2_round_replay(c2):
             continue
         gm.draft(E, d)
         gm.verify(E, d)
-        D, V, _, _, n_acc = gm.peek_round(d)
+        D, V, dmarg, _, n_acc = gm.peek_round(d)
         kd = next((i for i, g in enumerate(r.draft_margins) if g < NEAR_TIE), d)
+        # bf16 rounding noise moves a margin by up to ~1e-2 at this width (pinned on the CPU in
+        # test_oracle_invariants): a draft that differs where the oracle's margin is just above the
+        # threshold and the GPU's own margin is below it is a near-tie seen from the other side
+        kg = next((i for i in range(kd) if D[i] != r.draft[i]), kd)
+        if kg < kd:
+            assert r.draft_margins[kg] < 2.5 * NEAR_TIE and dmarg[kg] < NEAR_TIE, (kg, r.draft_margins, dmarg)
+            gpu_side_ties += 1
+            kd = kg
         assert D[:kd] == r.draft[:kd]
         for i in range(kd + 1 if kd < d else d + 1):
             if r.verify_margins[i] >= NEAR_TIE and D[:i] == r.draft[:i]:
@@ -101,3 +110,4 @@ def test_c2_round_replay(c2):
         if kd == d and all(g >= NEAR_TIE for g in r.verify_margins):
             assert n_acc == r.n_accept
     assert checked >= 3
+    assert gpu_side_ties <= 1

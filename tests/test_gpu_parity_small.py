@@ -53,7 +53,10 @@ def test_generate_matches_oracle_and_full_greedy(name):
     same_until_near_tie(ar, ref.tokens, ref.margins)
     assert toks == ar                       # the GPU path is lossless against its own full greedy
     assert st_ar.rounds == 0 and st.drafted == st.rounds * w.draft_len
-    if n == w.n_new:                        # no divergence: the round statistics must agree too
+    # no divergence and no near-tie among the oracle's drafts (a draft that flips at a near-tie leaves
+    # the tokens alone but changes how many are accepted): the round statistics must agree too
+    tight = all(g >= NEAR_TIE for r in ref.rounds for g in r.draft_margins)
+    if n == w.n_new and (tight or w.model.dtype == "f32"):
         assert (st.rounds, st.accepted) == (len(ref.rounds), ref.accepted)
     gm.close()
 
