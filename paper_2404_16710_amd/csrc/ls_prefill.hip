@@ -100,6 +100,26 @@ struct PfGemm {
   int hd, pos0, max_seq, nkv, layer;
 };
 
+// Which output tile a workgroup computes.  Workgroups are dealt round-robin to the 8 dies, each with
+// an L2 of its own, so the ids that are congruent mod 8 are renumbered consecutively and walk the
+// tile grid in panels of 4 tile columns, row by row: the workgroups that run together on a die then
+// cover a compact block of tiles (for the 7B prompt exactly 12 x 4), and every A and W tile is
+// fetched from memory once per die and panel instead of once per workgroup.  (If the dealing were
+// different, the map would still be a bijection; only the locality would suffer.)
+__device__ __forceinline__ void pf_tile_of(int MT, int NT, int& tm, int& tn) {
+  constexpr int NX = 8, PN = 4;
+  const int total = MT * NT, id = (int)blockIdx.x;
+  const int x = id % NX, local = id / NX;
+  int base = 0;
+  for (int y = 0; y < x; ++y) base += (total - y + NX - 1) / NX;
+  const int lin = base + local;
+  const int panel = lin / (MT * PN), n_first = panel * PN;
+  const int pw = NT - n_first < PN ? NT - n_first : PN;
+  const int r = lin - panel * MT * PN;
+  tm = r / pw;
+  tn = n_first + (r - tm * pw);
+}
+
 constexpr int BM = 128, BN = 128;
 constexpr int ROWB = 128;          // bytes of K per tile row
 constexpr int ROWP = ROWB + 16;    // padded LDS row
@@ -113,7 +133,9 @@ __global__ __launch_bounds__(256) void pf_gemm_kernel(const PfGemm g) {
   __shared__ __align__(16) char Ws[NW][BN * ROWP];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, gq = lane >> 4;
-  const int n0 = blockIdx.x * BN, m0 = blockIdx.y * BM;
+  int tile_m, tile_n;
+  pf_tile_of((g.M + BM - 1) / BM, (g.N + BN - 1) / BN, tile_m, tile_n);
+  const int n0 = tile_n * BN, m0 = tile_m * BM;
   const T* Ag = static_cast<const T*>(g.A);
   const T* Wg[2] = {static_cast<const T*>(g.W), static_cast<const T*>(g.W2)};
 
@@ -252,7 +274,9 @@ __global__ __launch_bounds__(256) void pf_gemm_ks_kernel(const PfGemm g) {
   char* Ws = ks_smem + SBM * SROWP;   // [NW][BN][SROWP]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, gq = lane >> 4;
-  const int n0 = blockIdx.x * BN, m0 = blockIdx.y * SBM;
+  int tile_m, tile_n;
+  pf_tile_of((g.M + SBM - 1) / SBM, (g.N + BN - 1) / BN, tile_m, tile_n);
+  const int n0 = tile_n * BN, m0 = tile_m * SBM;
   const T* Ag = static_cast<const T*>(g.A);
   const T* Wg[2] = {static_cast<const T*>(g.W), static_cast<const T*>(g.W2)};
 
@@ -408,11 +432,11 @@ hipError_t launch_gemm(const PfGemm& g, hipStream_t s) {
       if (e != hipSuccess) return e;
       configured = true;
     }
-    dim3 grid((g.N + BN - 1) / BN, (g.M + SBM - 1) / SBM);
+    dim3 grid(((g.N + BN - 1) / BN) * ((g.M + SBM - 1) / SBM));
     pf_gemm_ks_kernel<T, EPI><<<grid, dim3(256), smem, s>>>(g);
     return hipGetLastError();
   }
-  dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM);
+  dim3 grid(((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM));
   pf_gemm_kernel<T, EPI><<<grid, dim3(256), 0, s>>>(g);
   return hipGetLastError();
 }
