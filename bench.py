@@ -116,6 +116,15 @@ def main() -> int:
     nr_toks, nr = model.generate_no_reuse(prompt, w.n_new, E, d)
     model.generate_early_exit(prompt, w.n_new, E)
     _, ee = model.generate_early_exit(prompt, w.n_new, E)
+    # NEXT row of the scope table: per-token exit layer (a draft leaves at E/2 when its margin reaches tau)
+    dyn = None
+    if E >= 2:
+        e_low, tau = max(1, E // 2), 0.05
+        dy_toks, dy, _, dy_low = model.generate_dynamic(prompt, w.n_new, e_low, E, d, tau)
+        dyn = {"exit_low": e_low, "exit_high": E, "tau": tau,
+               "decode_tokens_per_s": round((w.n_new - 1) / (dy.ms_decode * 1e-3), 2),
+               "ms_decode": round(dy.ms_decode, 3), "acceptance": round(dy.acceptance, 4), "rounds": dy.rounds,
+               "drafts_leaving_at_exit_low": round(dy_low / max(dy.drafted, 1), 4), "same_ids": bool(dy_toks == toks)}
 
     # the stages on their own, through the step-by-step calls (one launch each, timed with events on
     # the launch stream): ls_draft = d draft steps + the early-layer pass of the last draft, ls_verify =
@@ -184,6 +193,7 @@ def main() -> int:
                            "reuse_saves_ms_per_token": round((nr.ms_decode - ms_dec) / (w.n_new - 1), 4)},
         "early_exit_only": {"decode_tokens_per_s": round((w.n_new - 1) / (ee.ms_decode * 1e-3), 2),
                             "ms_decode": round(ee.ms_decode, 3), "exit_layer": E},
+        "per_token_exit_layer": dyn,
         "stages": {"draft_launch": {"ms": round(float(np.mean(t_draft)), 3), "hbm_gbs": round(gb(b_draft, t_draft), 1),
                                     "hbm_frac": round(gb(b_draft, t_draft) / HBM_PEAK_GBS, 4),
                                     "what": f"{d} draft steps + early layers of the last draft (ls_draft)"},

@@ -132,6 +132,21 @@ int ls_generate_no_reuse(ls_ctx *ctx, const int32_t *dev_prompt, int32_t n_promp
                          int32_t exit_layer, int32_t draft_len, int32_t eos_token,
                          int32_t *dev_out_tokens, ls_stats *host_stats, void *stream);
 
+/* Self-speculative decoding with a per-token exit layer, the extension the paper's closing section
+ * names ("dynamic conditions to determine a different exit layer for each token"); the paper gives
+ * no algorithm, the reading implemented is: a draft leaves at layer exit_low when the margin between
+ * the two largest logits of g(x_{exit_low}) is at least tau, otherwise it continues to exit_high
+ * (1 <= exit_low < exit_high <= L); rows that left early pass through layers exit_low..exit_high-1
+ * later, several rows per pass, so that verification (from exit_high, Section 4.3.2) and the
+ * output tokens are exactly those of ls_generate(exit_layer = exit_high).  tau = +inf never leaves
+ * early; tau <= 0 always does.  dev_exit_layers (DEVICE int32[max_new * d], or NULL) receives the
+ * exit layer of every draft, round by round; *host_low_exits (HOST, or NULL) the number of drafts
+ * that left at exit_low.  Otherwise as ls_generate with d >= 1. */
+int ls_generate_dynamic(ls_ctx *ctx, const int32_t *dev_prompt, int32_t n_prompt, int32_t max_new,
+                        int32_t exit_low, int32_t exit_high, int32_t draft_len, float tau,
+                        int32_t eos_token, int32_t *dev_out_tokens, int32_t *dev_exit_layers,
+                        ls_stats *host_stats, int64_t *host_low_exits, void *stream);
+
 /* Early exit on its own (Section 4.2): like ls_generate with d = 0, but every pass, the prefill
  * included, runs layers 0..exit_layer-1 only and predicts with g(x_E). */
 int ls_generate_early_exit(ls_ctx *ctx, const int32_t *dev_prompt, int32_t n_prompt,

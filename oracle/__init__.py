@@ -13,6 +13,7 @@ from .decoder import (  # noqa: F401
     argmax_lowest, top2_margin, round_to_bf16, bf16_bits_to_float,
 )
 from .selfspec import (  # noqa: F401
-    greedy_full, self_speculative, early_exit_greedy, layer_probe, prefill, DecodeResult, RoundTrace,
+    greedy_full, self_speculative, self_speculative_dynamic, early_exit_greedy, layer_probe, prefill,
+    DecodeResult, RoundTrace,
 )
 from .bruteforce import forward_nocache, greedy_nocache  # noqa: F401

@@ -40,6 +40,7 @@ class RoundTrace:
     n_accept: int
     draft_margins: List[float]
     verify_margins: List[float]
+    exit_layers: Optional[List[int]] = None   # per draft, when the exit layer is chosen per token
 
 
 @dataclass
@@ -150,6 +151,84 @@ def self_speculative(model: OracleModel, prompt, n_new: int, exit_layer: int, d:
         last = V[n]
         if round_hook is not None:
             round_hook(cache, pos, list(out))
+    return res
+
+
+def self_speculative_dynamic(model: OracleModel, prompt, n_new: int, e_low: int, e_high: int, d: int,
+                             tau: float, max_seq: Optional[int] = None) -> DecodeResult:
+    """Self-speculative decoding with a per-token exit layer (the extension the paper's closing section
+    names as future work: "dynamic conditions to determine a different exit layer for each token").
+
+    The paper gives no algorithm; the reading taken here keeps everything of Section 4.3 and lets a
+    draft leave at one of two layers:
+      * a draft first exits at layer e_low; if the top-1 / top-2 logit margin of g(x_{e_low}) is at
+        least tau, that prediction is the draft token;
+      * otherwise the token continues through layers e_low..e_high-1 and g(x_{e_high}) drafts it.
+        Layers e_low..e_high-1 need the keys and values of every earlier position, so the rows that
+        left early since the last deep draft go through those layers in the same pass (one pass for
+        several rows, like verification);
+      * before verification the rows still pending (the last draft's row always is) are taken through
+        layers e_low..e_high-1 in one pass; verification then is that of Section 4.3.2 from layer e_high.
+    Every row ends up with exactly the states and cache entries of a fixed exit at e_high, whatever
+    was decided along the way, so the output is full-model greedy as before; tau = +inf is
+    `self_speculative(exit_layer=e_high)` and tau <= 0 drafts like `self_speculative(exit_layer=e_low)`.
+    `rounds[k].exit_layers` records where each draft left.
+    """
+    L = model.cfg.n_layers
+    assert 1 <= e_low < e_high <= L and d >= 1
+    P = len(prompt)
+    cache = model.new_cache(max_seq or (P + n_new + d + 1))
+    logits = prefill(model, prompt, cache)
+    out, margins = [argmax_lowest(logits)], [top2_margin(logits)]
+    pos, last = P, out[0]
+    res = DecodeResult(out, margins)
+    while len(out) < n_new:
+        D, dm_, exits = [], [], []
+        X = [None] * (d + 1)       # row i: the state of the round's i-th token at the deepest layer it has reached
+        j0 = 0                     # rows j0.. have only been through layers 0..e_low-1
+        u = last
+
+        def deepen(upto):
+            rows = np.stack(X[j0:upto + 1], axis=0)
+            y = model.run_layers(rows, list(range(pos + j0, pos + upto + 1)), cache, e_low, e_high)
+            for k in range(j0, upto + 1):
+                X[k] = y[k - j0]
+
+        for i in range(d):
+            X[i] = model.run_layers(model.embed_tokens([u]), [pos + i], cache, 0, e_low)[0]
+            lg = model.head(X[i][None, :])[0]
+            g = top2_margin(lg)
+            if g >= tau:
+                exits.append(e_low)
+            else:
+                deepen(i)
+                j0 = i + 1
+                lg = model.head(X[i][None, :])[0]
+                g = top2_margin(lg)
+                exits.append(e_high)
+            D.append(argmax_lowest(lg))
+            dm_.append(g)
+            u = D[-1]
+        X[d] = model.run_layers(model.embed_tokens([D[-1]]), [pos + d], cache, 0, e_low)[0]
+        deepen(d)
+        xl = model.run_layers(np.stack(X, axis=0), list(range(pos, pos + d + 1)), cache, e_high, L)
+        lg = model.head(xl)
+        V = [argmax_lowest(lg[i]) for i in range(d + 1)]
+        vm = [top2_margin(lg[i]) for i in range(d + 1)]
+        n = 0
+        while n < d and D[n] == V[n]:
+            n += 1
+        emitted = D[:n] + [V[n]]
+        tr = RoundTrace(pos, last, D, V, n, dm_, vm)
+        tr.exit_layers = exits
+        res.rounds.append(tr)
+        res.drafted += d
+        res.accepted += n
+        room = n_new - len(out)
+        out.extend(emitted[:room])
+        margins.extend(vm[:n + 1][:room])
+        pos += n + 1
+        last = V[n]
     return res
 
 

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = (
     "ls_workspace_bytes", "ls_load_weights", "ls_prefill", "ls_draft", "ls_verify", "ls_generate",
-    "ls_generate_no_reuse", "ls_generate_early_exit", "ls_score", "ls_probe_layers", "ls_get_state", "ls_peek_round", "ls_debug_capture",
+    "ls_generate_no_reuse", "ls_generate_dynamic", "ls_generate_early_exit", "ls_score", "ls_probe_layers", "ls_get_state", "ls_peek_round", "ls_debug_capture",
     "ls_debug_timeline", "ls_debug_copy", "ls_set_launch", "ls_set_exchange", "ls_debug_spin_limit", "ls_strerror", "ls_destroy",
 )
 
@@ -92,6 +92,9 @@ def lib() -> C.CDLL:
     L.ls_verify.argtypes = [vp, i32, i32, vp]
     L.ls_generate.restype = C.c_int
     L.ls_generate.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, C.POINTER(ls_stats), vp]
+    L.ls_generate_dynamic.restype = C.c_int
+    L.ls_generate_dynamic.argtypes = [vp, vp, i32, i32, i32, i32, i32, C.c_float, i32, vp, vp, C.POINTER(ls_stats),
+                                      C.POINTER(C.c_int64), vp]
     L.ls_generate_no_reuse.restype = C.c_int
     L.ls_generate_no_reuse.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, C.POINTER(ls_stats), vp]
     L.ls_generate_early_exit.restype = C.c_int
@@ -248,6 +251,23 @@ class LsModel:
                "ls_generate_no_reuse")
         stats = Stats(st.rounds, st.drafted, st.accepted, st.generated, st.ms_prefill, st.ms_decode)
         return out.cpu().numpy()[: stats.generated].tolist(), stats
+
+    def generate_dynamic(self, prompt: Sequence[int], max_new: int, exit_low: int, exit_high: int, d: int, tau: float,
+                         eos_id: int = -1):
+        """Per-token exit layer.  Returns (tokens, stats, exit layer of every draft as rows of d, drafts that left
+        at exit_low)."""
+        p = self._dev_i32(prompt)
+        out = self.torch.empty(max_new, dtype=self.torch.int32, device=self.device)
+        exits = self.torch.zeros(max_new * d, dtype=self.torch.int32, device=self.device)
+        st = ls_stats()
+        low = C.c_int64(0)
+        _check(self.lib.ls_generate_dynamic(self.ctx, C.c_void_p(p.data_ptr()), len(prompt), max_new, exit_low, exit_high,
+                                            d, C.c_float(tau), eos_id, C.c_void_p(out.data_ptr()),
+                                            C.c_void_p(exits.data_ptr()), C.byref(st), C.byref(low), self._stream()),
+               "ls_generate_dynamic")
+        stats = Stats(st.rounds, st.drafted, st.accepted, st.generated, st.ms_prefill, st.ms_decode)
+        ex = exits.cpu().numpy()[: stats.rounds * d].reshape(stats.rounds, d).tolist()
+        return out.cpu().numpy()[: stats.generated].tolist(), stats, ex, int(low.value)
 
     def generate_early_exit(self, prompt: Sequence[int], max_new: int, exit_layer: int):
         p = self._dev_i32(prompt)

@@ -160,7 +160,7 @@ int launch(ls_ctx* c, LsKParams& p, hipStream_t s) {
 LsKParams program(const ls_ctx* c, int kind) {
   LsKParams p = c->base;
   p.kind = kind;
-  p.E = 0; p.d = 0; p.max_new = 0x7fffffff; p.eos = -1; p.n_tokens = 0; p.layers_used = c->cfg.n_layers;
+  p.E = 0; p.d = 0; p.E_low = 0; p.tau = 0.f; p.out_exits = nullptr; p.max_new = 0x7fffffff; p.eos = -1; p.n_tokens = 0; p.layers_used = c->cfg.n_layers;
   p.tokens = nullptr; p.out_tokens = nullptr; p.out_margin = nullptr;
   p.capture = c->capture;
   p.prof = c->prof; p.prof_cap = c->prof_cap; p.prof_wg = c->prof_wg;
@@ -394,9 +394,16 @@ int ls_verify(ls_ctx* c, int32_t E, int32_t d, void* stream) {
   return LS_OK;
 }
 
+struct DynamicExit {      // per-token exit layer (ls_generate_dynamic)
+  int32_t E_low = 0;
+  float tau = 0.f;
+  int32_t* dev_exits = nullptr;
+  int64_t* low_exits = nullptr;
+};
+
 static int generate_impl(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, int32_t max_new, int32_t E, int32_t d,
                          int32_t eos, int32_t layers_used, int32_t* dev_out, ls_stats* stats, void* stream,
-                         bool no_reuse = false) {
+                         bool no_reuse = false, const DynamicExit* dyn = nullptr) {
   if (!c || !dev_prompt || !dev_out) return LS_E_ARG;
   if (n_prompt < 1 || max_new < 1) return LS_E_RANGE;
   if (d < 0 || d > c->cfg.max_draft) return LS_E_RANGE;
@@ -414,6 +421,7 @@ static int generate_impl(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt,
   LsKParams g = program(c, LS_PROG_GENERATE);
   g.E = E; g.d = d; g.max_new = max_new; g.eos = eos; g.out_tokens = dev_out; g.layers_used = layers_used;
   g.no_reuse = no_reuse ? 1 : 0;
+  if (dyn) { g.E_low = dyn->E_low; g.tau = dyn->tau; g.out_exits = dyn->dev_exits; }
   rc = launch(c, g, s);
   if (rc != LS_OK) return rc;
   if (hipEventRecord(c->ev[2], s) != hipSuccess) return LS_E_HIP;
@@ -421,6 +429,7 @@ static int generate_impl(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt,
   rc = read_state(c, &st, s);
   if (rc != LS_OK) return rc;
   c->prefilled = true; c->drafted = false; c->pos_bound = st.pos;
+  if (dyn && dyn->low_exits) *dyn->low_exits = st.low_exits;
   if (stats) {
     stats->rounds = st.rounds; stats->drafted = st.drafted; stats->accepted = st.accepted; stats->generated = st.n_gen;
     stats->ms_prefill = stats->ms_decode = 0.f;
@@ -441,6 +450,16 @@ int ls_generate_no_reuse(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt,
   if (!c) return LS_E_ARG;
   if (d < 1) return LS_E_RANGE;
   return generate_impl(c, dev_prompt, n_prompt, max_new, E, d, eos, c->cfg.n_layers, dev_out, stats, stream, true);
+}
+
+int ls_generate_dynamic(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, int32_t max_new, int32_t E_low,
+                        int32_t E_high, int32_t d, float tau, int32_t eos, int32_t* dev_out, int32_t* dev_exit_layers,
+                        ls_stats* stats, int64_t* host_low_exits, void* stream) {
+  if (!c) return LS_E_ARG;
+  if (d < 1 || E_low < 1 || E_low >= E_high || E_high > c->cfg.n_layers || tau != tau) return LS_E_RANGE;
+  DynamicExit dyn;
+  dyn.E_low = E_low; dyn.tau = tau; dyn.dev_exits = dev_exit_layers; dyn.low_exits = host_low_exits;
+  return generate_impl(c, dev_prompt, n_prompt, max_new, E_high, d, eos, c->cfg.n_layers, dev_out, stats, stream, false, &dyn);
 }
 
 int ls_generate_early_exit(ls_ctx* c, const int32_t* dev_prompt, int32_t n_prompt, int32_t max_new, int32_t E,

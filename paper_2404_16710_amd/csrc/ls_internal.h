@@ -40,6 +40,7 @@ struct LsState {
   int32_t draft_E, draft_d;
   int32_t n_emit;      // tokens the last round emitted (before the max_new cut)
   int64_t rounds, drafted, accepted;
+  int64_t low_exits;   // drafts that left at the lower of two exit layers (per-token exit layer)
   int32_t D[LS_ROWS];
   int32_t V[LS_ROWS];
   float dmargin[LS_ROWS];
@@ -84,6 +85,9 @@ struct LsKParams {
   int32_t kind, E, d, max_new, eos, n_tokens, layers_used;
   int32_t probe;      // LS_PROG_SCORE: argmax of the head after every layer, outputs [layer][row]
   int32_t no_reuse;   // rounds verify with all L layers instead of continuing from the exit states (ablation)
+  int32_t E_low;      // > 0: per-token exit layer, a draft leaves at E_low when its margin is at least tau, else at E
+  float tau;
+  int32_t *out_exits; // [rounds][d] exit layer of every draft, or null
   const int32_t *tokens;
   int32_t *out_tokens;
   float *out_margin;

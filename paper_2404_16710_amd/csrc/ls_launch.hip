@@ -43,7 +43,7 @@ static int kernel_index(const LsKParams* p) {
     default: break;
   }
   if (p->d == 0) return p->layers_used == p->L ? LS_K_GREEDY : LS_K_AUX;
-  return p->no_reuse ? LS_K_AUX : LS_K_DECODE;
+  return (p->no_reuse || p->E_low > 0) ? LS_K_AUX : LS_K_DECODE;
 }
 
 extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid, hipStream_t stream) {

@@ -318,6 +318,55 @@ def test_generation_without_cache_reuse_matches(name):
     gm.close()
 
 
+@pytest.mark.parametrize("name", ["c1", "gqa-hd128-bf16", "gqa2-f32"])
+def test_per_token_exit_layer_matches(name):
+    """ls_generate_dynamic (a draft leaves at the lower of two exit layers when its margin reaches tau):
+    the tokens are those of ls_generate exactly, whatever tau; tau = inf reproduces ls_generate's rounds;
+    tau = 0 those of ls_generate at the lower exit; in between, the exit layers agree with the oracle's
+    as long as the sequences agree and no margin sits within the near-tie distance of tau."""
+    import math
+    w = CASES[name]
+    ws, prompt, om, gm = _setup(w)
+    L = w.model.n_layers
+    e_high = max(2, w.exit_layer)
+    e_low = e_high - 1
+    d = w.draft_len
+    assert e_high < L or e_high == L
+    toks, st = gm.generate(prompt, w.n_new, e_high, d)
+    t_inf, s_inf, ex_inf, low_inf = gm.generate_dynamic(prompt, w.n_new, e_low, e_high, d, math.inf)
+    assert t_inf == toks and (s_inf.rounds, s_inf.accepted) == (st.rounds, st.accepted)
+    assert low_inf == 0 and all(e == e_high for r in ex_inf for e in r)
+    t_lo, s_lo = gm.generate(prompt, w.n_new, e_low, d)
+    t_0, s_0, ex_0, low_0 = gm.generate_dynamic(prompt, w.n_new, e_low, e_high, d, 0.0)
+    assert t_0 == toks == t_lo and (s_0.rounds, s_0.accepted) == (s_lo.rounds, s_lo.accepted)
+    assert low_0 == s_0.drafted and all(e == e_low for r in ex_0 for e in r)
+    ref_lo = O.self_speculative(om, prompt, w.n_new, e_low, d)
+    margins = sorted(x for t in ref_lo.rounds for x in t.draft_margins)
+    tau = float(margins[len(margins) // 2])
+    ref = O.self_speculative_dynamic(om, prompt, w.n_new, e_low, e_high, d, tau)
+    got, sg, ex, low = gm.generate_dynamic(prompt, w.n_new, e_low, e_high, d, tau)
+    assert got == toks                                   # lossless against the GPU's own greedy path
+    same_until_near_tie(got, ref.tokens, ref.margins)
+    assert 0 < low < sg.drafted and low == sum(e == e_low for r in ex for e in r)
+    # round by round while both sides are in the same state and decide far from the threshold
+    # draft by draft while both sides are in the same state and the oracle decides far from the
+    # threshold and far from a tie (after the first decision that may differ, nothing is comparable)
+    eps = 1e-4 if w.model.dtype == "f32" else NEAR_TIE
+    compared, comparable = 0, True
+    for k, t in enumerate(ref.rounds):
+        if not comparable or k >= len(ex):
+            break
+        for i in range(d):
+            if abs(t.draft_margins[i] - tau) < eps or t.draft_margins[i] < eps:
+                comparable = False
+                break
+            assert ex[k][i] == t.exit_layers[i], (k, i, ex[k], t.exit_layers)
+            compared += 1
+        comparable = comparable and all(mg >= eps for mg in t.verify_margins)
+    assert compared >= 1
+    gm.close()
+
+
 @pytest.mark.parametrize("name", ["c1", "c1-bf16", "gqa2-f32"])
 def test_layer_probe_matches_oracle(name):
     """ls_probe_layers: argmax of g(x_l) after every layer for every row of a 40-token sequence (two

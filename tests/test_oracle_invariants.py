@@ -49,6 +49,45 @@ def test_verifying_without_cache_reuse_changes_nothing_but_the_work(c1, E, d):
     assert [(r.pos, r.draft, r.verify, r.n_accept) for r in b.rounds] == [(r.pos, r.draft, r.verify, r.n_accept) for r in a.rounds]
 
 
+@pytest.mark.parametrize("e_low,e_high,d", [(1, 2, 4), (1, 3, 5), (2, 4, 3)])
+def test_per_token_exit_layer_is_lossless_and_reduces_to_the_fixed_exits(c1, e_low, e_high, d):
+    """The per-token exit layer (the paper's closing section; reading in self_speculative_dynamic):
+    whatever the threshold, every row ends up with the states of a fixed exit at e_high, so the
+    output is full-model greedy; a threshold nobody reaches is self_speculative(e_high) round for
+    round; a threshold everybody reaches drafts like self_speculative(e_low); in between, a draft
+    that left early carries the early head's token and margin, a deep one the deep head's."""
+    w, m, p = _model(c1)
+    g = O.greedy_full(m, p, w.n_new)
+    hi = O.self_speculative(m, p, w.n_new, e_high, d)
+    lo = O.self_speculative(m, p, w.n_new, e_low, d)
+    key = lambda r: [(t.pos, t.draft, t.verify, t.n_accept) for t in r.rounds]
+    never = O.self_speculative_dynamic(m, p, w.n_new, e_low, e_high, d, math.inf)
+    assert never.tokens == g.tokens and key(never) == key(hi)
+    assert all(e == e_high for t in never.rounds for e in t.exit_layers)
+    always = O.self_speculative_dynamic(m, p, w.n_new, e_low, e_high, d, 0.0)
+    assert always.tokens == g.tokens and key(always) == key(lo)
+    assert all(e == e_low for t in always.rounds for e in t.exit_layers)
+    margins = sorted(x for t in lo.rounds for x in t.draft_margins)
+    tau = margins[len(margins) // 2]                      # about half of the first drafts are confident
+    mid = O.self_speculative_dynamic(m, p, w.n_new, e_low, e_high, d, tau)
+    assert mid.tokens == g.tokens
+    exits = [e for t in mid.rounds for e in t.exit_layers]
+    assert e_low in exits and e_high in exits
+    for t in mid.rounds:
+        for e, mg in zip(t.exit_layers, t.draft_margins):
+            assert (mg >= tau) if e == e_low else True    # early leavers met the threshold at e_low
+        assert t.draft[:t.n_accept] == t.verify[:t.n_accept]
+    # a round of `mid` that starts where a round of `hi` starts verifies to the same tokens as far as
+    # the drafts agree: verification does not depend on where the drafts left
+    by_pos = {t.pos: t for t in hi.rounds}
+    shared = [t for t in mid.rounds if t.pos in by_pos]
+    assert shared
+    for t in shared:
+        h = by_pos[t.pos]
+        k = next((i for i in range(d) if t.draft[i] != h.draft[i]), d)
+        assert t.verify[:k + 1] == h.verify[:k + 1]
+
+
 def test_layer_probe_agrees_with_brute_force_and_with_early_exit(c1):
     """The per-layer probe (Section 3) is the head applied to x_1..x_L: row by row it must equal the
     argmax of g over the states of the cache-free recomputation, its last layer is the full model, and
