@@ -125,7 +125,7 @@ constexpr int ROWB = 128;          // bytes of K per tile row
 constexpr int ROWP = ROWB + 16;    // padded LDS row
 
 template <typename T, int EPI>
-__global__ __launch_bounds__(256) void pf_gemm_kernel(const PfGemm g) {
+__global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
   constexpr int EPV = PT<T>::EPV;
   constexpr int BK = ROWB / (int)sizeof(T);
   constexpr int NW = (EPI == EPI_GU) ? 2 : 1;
@@ -265,7 +265,7 @@ constexpr int ks_smem_bytes() {
 }
 
 template <typename T, int EPI>
-__global__ __launch_bounds__(256) void pf_gemm_ks_kernel(const PfGemm g) {
+__global__ __launch_bounds__(256, 2) void pf_gemm_ks_kernel(const PfGemm g) {
   constexpr int EPV = PT<T>::EPV;
   constexpr int BK = SROWB / (int)sizeof(T);
   constexpr int NW = (EPI == EPI_GU) ? 2 : 1;
