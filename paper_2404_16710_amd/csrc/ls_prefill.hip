@@ -124,40 +124,48 @@ constexpr int BM = 128, BN = 128;
 constexpr int ROWB = 128;          // bytes of K per tile row
 constexpr int ROWP = ROWB + 16;    // padded LDS row
 
-template <typename T, int EPI>
+// BMT: rows of the output tile (128, or 64 when there are too few 128-row tiles to keep several
+// workgroups resident per compute unit); a wave computes BMT/4 rows x 128 columns.
+template <typename T, int EPI, int BMT>
 __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
   constexpr int EPV = PT<T>::EPV;
   constexpr int BK = ROWB / (int)sizeof(T);
   constexpr int NW = (EPI == EPI_GU) ? 2 : 1;
-  __shared__ __align__(16) char As[BM * ROWP];
+  constexpr int RT = BMT / 64;          // 16-row tiles per wave
+  constexpr int LA = BMT * 8 / 256;     // 16-byte units of the A tile per thread
+  __shared__ __align__(16) char As[BMT * ROWP];
   __shared__ __align__(16) char Ws[NW][BN * ROWP];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, gq = lane >> 4;
   int tile_m, tile_n;
-  pf_tile_of((g.M + BM - 1) / BM, (g.N + BN - 1) / BN, tile_m, tile_n);
-  const int n0 = tile_n * BN, m0 = tile_m * BM;
+  pf_tile_of((g.M + BMT - 1) / BMT, (g.N + BN - 1) / BN, tile_m, tile_n);
+  const int n0 = tile_n * BN, m0 = tile_m * BMT;
   const T* Ag = static_cast<const T*>(g.A);
   const T* Wg[2] = {static_cast<const T*>(g.W), static_cast<const T*>(g.W2)};
 
-  f32x4 acc[NW][2][8];
+  f32x4 acc[NW][RT][8];
 #pragma unroll
   for (int w = 0; w < NW; ++w)
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < RT; ++i)
 #pragma unroll
       for (int j = 0; j < 8; ++j) acc[w][i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  uint4 ra[4], rw[NW][4];
+  uint4 ra[LA], rw[NW][4];
   auto gload = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+      const int unit = tid + 256 * i, row = unit >> 3, u = unit & 7;
+      const int k = k0 + u * EPV, ma = m0 + row;
+      const bool aok = k < g.K && ma < g.M;
+      const uint4 va = *reinterpret_cast<const uint4*>(Ag + (size_t)(aok ? ma : 0) * g.lda + (aok ? k : 0));
+      ra[i] = aok ? va : make_uint4(0, 0, 0, 0);
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int unit = tid + 256 * i, row = unit >> 3, u = unit & 7;
-      const int k = k0 + u * EPV;
-      const bool kok = k < g.K;
-      const int ma = m0 + row, na = n0 + row;
-      const bool aok = kok && ma < g.M, wok = kok && na < g.N;
-      const uint4 va = *reinterpret_cast<const uint4*>(Ag + (size_t)(aok ? ma : 0) * g.lda + (aok ? k : 0));
-      ra[i] = aok ? va : make_uint4(0, 0, 0, 0);
+      const int k = k0 + u * EPV, na = n0 + row;
+      const bool wok = k < g.K && na < g.N;
 #pragma unroll
       for (int w = 0; w < NW; ++w) {
         const uint4 vw = *reinterpret_cast<const uint4*>(Wg[w] + (size_t)(wok ? na : 0) * g.K + (wok ? k : 0));
@@ -167,9 +175,13 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
   };
   auto lstore = [&]() {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < LA; ++i) {
       const int unit = tid + 256 * i, row = unit >> 3, u = unit & 7;
       *reinterpret_cast<uint4*>(As + row * ROWP + u * 16) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int unit = tid + 256 * i, row = unit >> 3, u = unit & 7;
 #pragma unroll
       for (int w = 0; w < NW; ++w) *reinterpret_cast<uint4*>(Ws[w] + row * ROWP + u * 16) = rw[w][i];
     }
@@ -183,17 +195,17 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
     if (k0 + BK < g.K) gload(k0 + BK);
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      uint4 fa[2];
+      uint4 fa[RT];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        fa[i] = *reinterpret_cast<const uint4*>(As + (wave * 32 + i * 16 + r) * ROWP + (s * 4 + gq) * 16);
+      for (int i = 0; i < RT; ++i)
+        fa[i] = *reinterpret_cast<const uint4*>(As + (wave * (16 * RT) + i * 16 + r) * ROWP + (s * 4 + gq) * 16);
 #pragma unroll
       for (int w = 0; w < NW; ++w) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const uint4 fb = *reinterpret_cast<const uint4*>(Ws[w] + (j * 16 + r) * ROWP + (s * 4 + gq) * 16);
 #pragma unroll
-          for (int i = 0; i < 2; ++i) PT<T>::mma(acc[w][i][j], fa[i], fb);
+          for (int i = 0; i < RT; ++i) PT<T>::mma(acc[w][i][j], fa[i], fb);
         }
       }
     }
@@ -202,10 +214,10 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
   // epilogue: the lane holds rows m = base + 4*gq + jj (jj = 0..3) of column n = n0 + 16*j + r
   const int half = g.hd / 2;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < RT; ++i) {
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
-      const int m = m0 + wave * 32 + i * 16 + 4 * gq + jj;
+      const int m = m0 + wave * (16 * RT) + i * 16 + 4 * gq + jj;
       if (m >= g.M) continue;
       const int pos = g.pos0 + m;
 #pragma unroll
@@ -436,8 +448,17 @@ hipError_t launch_gemm(const PfGemm& g, hipStream_t s) {
     pf_gemm_ks_kernel<T, EPI><<<grid, dim3(256), smem, s>>>(g);
     return hipGetLastError();
   }
-  dim3 grid(((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM));
-  pf_gemm_kernel<T, EPI><<<grid, dim3(256), 0, s>>>(g);
+  // 64-row tiles while 128-row tiles would leave fewer than about two per compute unit
+  const long tiles128 = (long)((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM);
+  static const int forced_rows = []() { const char* v = getenv("LS_PF_TILE_ROWS"); return v ? atoi(v) : 0; }();   // tuning aid
+  const bool rows64 = forced_rows == 64 || (forced_rows != 128 && tiles128 < 600);
+  if (rows64) {
+    dim3 grid(((g.N + BN - 1) / BN) * ((g.M + 63) / 64));
+    pf_gemm_kernel<T, EPI, 64><<<grid, dim3(256), 0, s>>>(g);
+  } else {
+    dim3 grid(((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM));
+    pf_gemm_kernel<T, EPI, 128><<<grid, dim3(256), 0, s>>>(g);
+  }
   return hipGetLastError();
 }
 
