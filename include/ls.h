@@ -209,6 +209,14 @@ int ls_set_launch(ls_ctx *ctx, int32_t workgroups_per_cu);
  * result is discarded.  Returns LS_OK or a negative error. */
 int ls_set_exchange(ls_ctx *ctx, int32_t max_tagged_rows);
 
+/* Shape of the prompt pass used by later calls.  Prompts of 32 or more ids run as GEMMs over all
+ * rows of a chunk, with output tiles of 128, 64 or 32 rows chosen from the number of tiles the
+ * launch would have (rows = 0, the default); 32, 64 or 128 force that tile height, 16 sends every
+ * prompt through the 16-row passes of the decode kernel.  All choices compute the same operation
+ * and differ in the order of the floating-point sums only.  Host state only: no GPU work.
+ * Returns LS_OK, LS_E_ARG for a null context or LS_E_RANGE for any other value. */
+int ls_set_prompt_tiles(ls_ctx *ctx, int32_t rows);
+
 const char *ls_strerror(int code);
 
 /* Frees the host object only; the workspace and the weights stay with the caller. */

@@ -300,7 +300,6 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   f.x_pf = reinterpret_cast<float*>(c->ws + lay.x_pf); f.a_pf = c->ws + lay.a_pf; f.q_pf = c->ws + lay.q_pf;
   f.o_pf = c->ws + lay.o_pf; f.act_pf = c->ws + lay.act_pf; f.xbuf = p.xbuf; f.ssq = p.ssq;
   c->gemm_prefill = true;
-  if (const char* e = getenv("LS_PREFILL")) c->gemm_prefill = !(e[0] == 'r' || e[0] == '0');   // "rows": 16-row passes
   *out = c;
   return LS_OK;
 }
@@ -310,6 +309,14 @@ int ls_set_exchange(ls_ctx* c, int32_t max_tagged_rows) {
   if (max_tagged_rows < 0 || max_tagged_rows > LS_ROWS) return LS_E_RANGE;
   c->base.ll_max_rows = max_tagged_rows;
   c->drafted = false;   // exit states of a pending draft may be in the other representation
+  return LS_OK;
+}
+
+int ls_set_prompt_tiles(ls_ctx* c, int32_t rows) {
+  if (!c) return LS_E_ARG;
+  if (rows != 0 && rows != 16 && rows != 32 && rows != 64 && rows != 128) return LS_E_RANGE;
+  c->gemm_prefill = rows != 16;
+  c->pf.tile_rows = rows == 16 ? 0 : rows;
   return LS_OK;
 }
 

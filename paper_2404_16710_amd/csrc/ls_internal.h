@@ -120,6 +120,7 @@ struct LsPfParams {
   void *a_pf, *q_pf, *o_pf, *act_pf;  // [pf_rows][dm], [..][qd], [..][qd], [..][ffn] in the model dtype
   float *xbuf, *ssq;           // decode residual row 0 and its statistics (target of the finish step)
   float *capture;
+  int32_t tile_rows;           // rows of a prompt GEMM's output tile: 0 = by the number of tiles, else 32, 64 or 128
 };
 
 #endif

@@ -98,6 +98,7 @@ struct PfGemm {
   float* capture;   // optional copy of the new residual rows, [max_seq][N] of this layer
   const float* rope_cos; const float* rope_sin;
   int hd, pos0, max_seq, nkv, layer;
+  int tile_rows;    // 0: chosen from the number of tiles; 32, 64, 128: forced (host only)
 };
 
 // Which output tile a workgroup computes.  Workgroups are dealt round-robin to the 8 dies, each with
@@ -426,8 +427,7 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_ks_kernel(const PfGemm g) {
 // flight per workgroup), so the small tile's lower reuse only pays below about half a tile per
 // compute unit (measured on 256 CUs: 64 tiles 1.8x faster, 176 tiles 1.5x slower).
 static bool use_small_tiles(const PfGemm& g) {
-  static const int forced = []() { const char* v = getenv("LS_PF_SMALL_TILES"); return v ? atoi(v) : -1; }();   // tuning aid
-  if (forced >= 0) return forced != 0;
+  if (g.tile_rows) return g.tile_rows == SBM;
   const long tiles = (long)((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM);
   return tiles < 128;
 }
@@ -450,8 +450,7 @@ hipError_t launch_gemm(const PfGemm& g, hipStream_t s) {
   }
   // 64-row tiles while 128-row tiles would leave fewer than about two per compute unit
   const long tiles128 = (long)((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM);
-  static const int forced_rows = []() { const char* v = getenv("LS_PF_TILE_ROWS"); return v ? atoi(v) : 0; }();   // tuning aid
-  const bool rows64 = forced_rows == 64 || (forced_rows != 128 && tiles128 < 600);
+  const bool rows64 = g.tile_rows == 64 || (g.tile_rows != 128 && tiles128 < 600);
   if (rows64) {
     dim3 grid(((g.N + BN - 1) / BN) * ((g.M + 63) / 64));
     pf_gemm_kernel<T, EPI, 64><<<grid, dim3(256), 0, s>>>(g);
@@ -666,7 +665,7 @@ int run_layers(const LsPfParams& p, const LsLayerW* lw, int pos0, int M, hipStre
     pf_rmsnorm_kernel<T><<<dim3(M), dim3(256), 0, s>>>(p.x_pf, static_cast<const T*>(W.attn_norm), static_cast<T*>(p.a_pf), dm, p.eps);
     PfGemm g{};
     g.A = p.a_pf; g.lda = dm; g.M = M; g.K = dm; g.hd = p.hd; g.pos0 = pos0; g.max_seq = p.max_seq; g.nkv = p.nkv;
-    g.layer = l; g.rope_cos = p.rope_cos; g.rope_sin = p.rope_sin;
+    g.layer = l; g.rope_cos = p.rope_cos; g.rope_sin = p.rope_sin; g.tile_rows = p.tile_rows;
     g.W = W.wq; g.N = qd; g.out = p.q_pf; g.ldo = qd;
     if (launch_gemm<T, EPI_ROPE_Q>(g, s) != hipSuccess) return 1;
     g.W = W.wk; g.N = kvd; g.out = p.kcache;

@@ -211,6 +211,41 @@ def test_prefill_hidden_states_and_cache(name, n_prompt):
     gm.close()
 
 
+@pytest.mark.parametrize("name", ["c1", "c1-bf16", "gqa-hd128-bf16"])
+def test_every_prompt_pass_shape_matches_oracle(name):
+    """ls_set_prompt_tiles: the prompt GEMMs with 128-, 64- and 32-row output tiles and the 16-row
+    passes of the decode kernel, each forced on a prompt that spans several tiles of every height
+    with a ragged last one (300 = 2 x 128 + 44 = 4 x 64 + 44 = 9 x 32 + 12 = 18 x 16 + 12)."""
+    n_prompt = 300
+    w = CASES[name].with_(n_prompt=n_prompt)
+    ws, prompt, om, gm = _setup(w, max_seq=n_prompt + 64)
+    hid = []
+    cache = om.new_cache(n_prompt + 64)
+    xl = om.run_layers(om.embed_tokens(prompt), list(range(n_prompt)), cache, 0, w.model.n_layers, hid)
+    logits = om.head(xl[-1:])[0]
+    tol = 2e-2 if w.model.dtype == "bf16" else 1e-4
+    ref = O.self_speculative(om, prompt, 12, w.exit_layer, w.draft_len)
+    cap = gm.debug_capture(True)
+    from paper_2404_16710_amd.binding import LsError
+    with pytest.raises(LsError):
+        gm.set_prompt_tiles(48)
+    for rows in (128, 64, 32, 16, 0):
+        print(f"[prompt tiles] {name} rows {rows}", flush=True)
+        gm.set_prompt_tiles(rows)
+        cap.zero_()
+        gm.prefill(prompt)
+        pos, last, n_gen = gm.get_state()
+        assert (pos, n_gen) == (n_prompt, 1)
+        if O.top2_margin(logits) >= NEAR_TIE:
+            assert last == O.argmax_lowest(logits), rows
+        got = cap.cpu().numpy()[:, :n_prompt, :]
+        for l in range(w.model.n_layers):
+            assert rel_err_rows(got[l], hid[l]) < tol, (rows, l)
+        toks, _ = gm.generate(prompt, 12, w.exit_layer, w.draft_len)      # the same prompt pass, then decoding
+        same_until_near_tie(toks, ref.tokens, ref.margins)
+    gm.close()
+
+
 def test_exit_at_last_layer_accepts_everything_on_gpu():
     w = CASES["c1"]
     ws, prompt, om, gm = _setup(w)
