@@ -136,12 +136,6 @@ void set_decomposition(ls_ctx* c) {
   // the shorter weight stream gains)
   c->base.gs_x = g.d_model / 16 <= c->grid ? 16 : choose_tile_rows(g.d_model, c->grid);
   c->base.gs_ffn = choose_tile_rows(g.ffn_dim, c->grid);
-  if (const char* e = getenv("LS_TILE_ROWS")) {   // "x,ffn" (tuning aid)
-    int a = 0, b = 0;
-    if (sscanf(e, "%d,%d", &a, &b) == 2 && (a == 8 || a == 12 || a == 16) && (b == 8 || b == 12 || b == 16)) {
-      c->base.gs_x = a; c->base.gs_ffn = b;
-    }
-  }
   c->base.ssq_nt = (g.d_model + c->base.gs_x - 1) / c->base.gs_x;
   // attention work items: (kv head, C consecutive 64-position tiles), C the smallest count for
   // which a full cache gives at most one item per workgroup
@@ -230,10 +224,6 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   if (ls_kernel_setup(cfg->dtype == LS_BF16, cfg->head_dim, &nb) != 0 || nb < 1) { delete c; return LS_E_HIP; }
   c->max_wg_per_cu = nb > 2 ? 2 : nb;
   c->wg_per_cu = c->max_wg_per_cu;
-  if (const char* e = getenv("LS_WG_PER_CU")) {
-    const int v = atoi(e);
-    if (v >= 1 && v <= c->max_wg_per_cu) c->wg_per_cu = v;
-  }
   c->grid = c->n_cu * c->wg_per_cu;
   if (c->grid > kMaxGrid) c->grid = kMaxGrid;
 
@@ -287,9 +277,7 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   p.at = reinterpret_cast<uint64_t*>(c->ws + lay.at); p.ct = reinterpret_cast<uint64_t*>(c->ws + lay.ct);
   p.attn_cnt_ll = reinterpret_cast<uint32_t*>(c->ws + lay.attn_cnt_ll);
   p.ll_max_rows = 0;
-  if (const char* e = getenv("LS_TAGGED_ROWS")) { const int v = atoi(e); if (v >= 0 && v <= LS_ROWS) p.ll_max_rows = v; }
   p.spin_limit = 1 << 22;
-  if (const char* e = getenv("LS_SPIN_LIMIT")) { const int v = atoi(e); if (v > 0) p.spin_limit = v; }
   set_decomposition(c);
   c->host_layers = lw;
   LsPfParams& f = c->pf;
