@@ -9,7 +9,7 @@ import pytest
 
 import oracle as O
 import workloads as W
-from parity_util import same_until_near_tie, rel_err_rows, head_agrees, NEAR_TIE
+from parity_util import same_until_near_tie, rel_err_rows, near_tie_from_either_side, gpu_decisions, NEAR_TIE
 
 pytestmark = pytest.mark.gpu
 
@@ -32,15 +32,12 @@ def c2():
 
 def test_c2_generate_ids(c2):
     w, prompt, om, gm, ref = c2
-    cap = gm.debug_capture(True)
     toks, st = gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
-    last = cap[w.model.n_layers - 1].cpu().numpy()          # x_L of every position
-    gm.debug_capture(False)
     ar, _ = gm.generate(prompt, w.n_new, 0, 0)
-    P = len(prompt)
-    explain = lambda i, tok: head_agrees(om, last[P - 1 + i], tok)
-    n = same_until_near_tie(toks, ref.tokens, ref.margins, explain=explain)
-    same_until_near_tie(ar, ref.tokens, ref.margins, explain=explain)
+    stepped, gpu_margins = gpu_decisions(gm, prompt, w.n_new, w.exit_layer, w.draft_len)
+    assert stepped == toks
+    n = same_until_near_tie(toks, ref.tokens, ref.margins, gpu_margins=gpu_margins)
+    same_until_near_tie(ar, ref.tokens, ref.margins, gpu_margins=gpu_margins)
     print(f"[c2] {n}/{w.n_new} ids compared before a near-tie; gpu acceptance {st.acceptance:.3f}", flush=True)
     assert toks == ar
     assert len(toks) == w.n_new
@@ -56,13 +53,12 @@ def test_c2_teacher_forced_and_hidden_states(c2):
     am, mg = gm.score(seq)
     gm.debug_capture(False)
     firm = [i for i in range(w.n_new) if ref.margins[i] >= NEAR_TIE]
-    last = cap[w.model.n_layers - 1].cpu().numpy()
     bad = [(i, float(ref.margins[i]), float(mg[P - 1 + i])) for i in firm
-           if am[P - 1 + i] != ref.tokens[i] and not head_agrees(om, last[P - 1 + i], int(am[P - 1 + i]))]
+           if am[P - 1 + i] != ref.tokens[i] and not near_tie_from_either_side(ref.margins[i], mg[P - 1 + i])]
     assert not bad, bad   # (position, oracle margin, gpu margin)
-    vouched = [i for i in firm if am[P - 1 + i] != ref.tokens[i]]
-    assert len(vouched) <= 3, vouched     # such flips are rare
-    print(f"[c2] ids differing at oracle margin >= 1e-2 but explained by the gpu's hidden state: {vouched}", flush=True)
+    flipped = [i for i in firm if am[P - 1 + i] != ref.tokens[i]]
+    assert len(flipped) <= 3, flipped     # such flips are rare
+    print(f"[c2] ids differing at oracle margin >= 1e-2 while the gpu's own margin is a near-tie: {flipped}", flush=True)
     assert len(firm) >= int(0.8 * w.n_new)
     # hidden states of every layer at every position, from one oracle pass over the same sequence
     hid = []

@@ -11,7 +11,7 @@ import pytest
 
 import oracle as O
 import workloads as W
-from parity_util import same_until_near_tie, rel_err_rows, head_agrees, NEAR_TIE
+from parity_util import same_until_near_tie, rel_err_rows, gpu_decisions, NEAR_TIE
 
 pytestmark = pytest.mark.gpu
 
@@ -49,9 +49,9 @@ def test_large_width_prompt_states_and_first_ids(name):
         worst = max(worst, e)
         assert e < 2e-2, (l, e)
     print(f"[{name}] worst prompt hidden-state error {worst:.2e}", flush=True)
-    last = got[L - 1]
-    n = same_until_near_tie(toks[:N_REF], ref.tokens, ref.margins,
-                            explain=lambda i, tok: head_agrees(om, last[P - 1 + i], tok))
+    stepped, gpu_margins = gpu_decisions(gm, prompt, N_REF, E, d)
+    assert stepped == toks[:N_REF]
+    n = same_until_near_tie(toks[:N_REF], ref.tokens, ref.margins, gpu_margins=gpu_margins)
     print(f"[{name}] {n}/{N_REF} ids compared before a near-tie; gpu acceptance {st.acceptance:.3f}", flush=True)
     assert n >= 1
     ar, st_ar = gm.generate(prompt, w.n_new, 0, 0)
