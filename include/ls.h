@@ -133,8 +133,8 @@ int ls_generate_no_reuse(ls_ctx *ctx, const int32_t *dev_prompt, int32_t n_promp
                          int32_t *dev_out_tokens, ls_stats *host_stats, void *stream);
 
 /* Self-speculative decoding with a per-token exit layer, the extension the paper's closing section
- * names ("dynamic conditions to determine a different exit layer for each token"); the paper gives
- * no algorithm, the reading implemented is: a draft leaves at layer exit_low when the margin between
+ * names as future work (an exit layer chosen per token by a condition evaluated while decoding);
+ * the paper gives no algorithm, the reading implemented is: a draft leaves at layer exit_low when the margin between
  * the two largest logits of g(x_{exit_low}) is at least tau, otherwise it continues to exit_high
  * (1 <= exit_low < exit_high <= L); rows that left early pass through layers exit_low..exit_high-1
  * later, several rows per pass, so that verification (from exit_high, Section 4.3.2) and the

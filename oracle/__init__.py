@@ -10,7 +10,7 @@ acceptance rates, ROUGE-2 and exact-match numbers of the paper's tables.
 """
 from .decoder import (  # noqa: F401
     OracleModel, KVCache, rmsnorm, silu, softmax_lastaxis, rope_angles, apply_rope,
-    argmax_lowest, top2_margin, round_to_bf16, bf16_bits_to_float,
+    argmax_lowest, top2_margin, runner_up, round_to_bf16, bf16_bits_to_float,
 )
 from .selfspec import (  # noqa: F401
     greedy_full, self_speculative, self_speculative_dynamic, early_exit_greedy, layer_probe, prefill,

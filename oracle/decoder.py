@@ -97,6 +97,16 @@ def top2_margin(logits: np.ndarray) -> float:
     return float(part[1] - part[0])
 
 
+def runner_up(logits: np.ndarray) -> int:
+    """Index of the second-largest value: the lowest index that attains the largest value left once
+    the argmax (lowest index on ties) is set aside.  Bookkeeping for the tests' near-tie rule: which
+    other token a rounding-sized change of the logits could turn the decision into."""
+    best = argmax_lowest(logits)
+    rest = np.array(logits, dtype=np.float64, copy=True)
+    rest[best] = -np.inf
+    return int(np.argmax(rest))
+
+
 # ------------------------------------------------------------------------------- model
 
 class KVCache:

@@ -14,8 +14,8 @@ all L layers (the "Autoregressive" baseline of Section 6.2).
   cache crop (Appendix A.4): the cache keeps (prompt + emitted - 1) positions, i.e. the
     last emitted token has not been through the model yet.
 Readings taken where the paper leaves room:
-  * verification consumes 1 + d rows (the round's input token and the d drafts), as the
-    appendix passes "input + draft tokens" to the remainder; so the last draft needs its
+  * verification consumes 1 + d rows (the round's input token and the d drafts): the appendix
+    hands the remainder the round's input followed by the drafts; so the last draft needs its
     own early-layer pass (no LM head) and a round emits n+1 tokens, n = accepted drafts;
   * the cached "exit query" is the hidden state x_E of each drafted position;
   * the prompt is prefilled with the full model, whose greedy token is output #1;
@@ -28,7 +28,7 @@ from typing import List, Optional
 
 import numpy as np
 
-from .decoder import OracleModel, KVCache, argmax_lowest, top2_margin
+from .decoder import OracleModel, KVCache, argmax_lowest, top2_margin, runner_up
 
 
 @dataclass
@@ -41,6 +41,8 @@ class RoundTrace:
     draft_margins: List[float]
     verify_margins: List[float]
     exit_layers: Optional[List[int]] = None   # per draft, when the exit layer is chosen per token
+    draft_runner_up: Optional[List[int]] = None    # second-best token of each draft decision
+    verify_runner_up: Optional[List[int]] = None   # ... of each verified decision
 
 
 @dataclass
@@ -51,6 +53,7 @@ class DecodeResult:
     drafted: int = 0
     accepted: int = 0
     hidden: Optional[np.ndarray] = None     # [L+1, positions, d_model] when requested
+    runner_up: List[int] = field(default_factory=list)   # second-best token of the decision behind each token
 
     @property
     def acceptance(self) -> float:
@@ -78,7 +81,7 @@ def greedy_full(model: OracleModel, prompt, n_new: int, max_seq: Optional[int] =
     per_pos = None
     if want_hidden:
         per_pos = [np.stack(hid, axis=0)]            # [L+1, P, dm]
-    tokens, margins = [argmax_lowest(logits)], [top2_margin(logits)]
+    tokens, margins, second = [argmax_lowest(logits)], [top2_margin(logits)], [runner_up(logits)]
     while len(tokens) < n_new:
         t = P + len(tokens) - 1
         x = model.embed_tokens([tokens[-1]])
@@ -89,7 +92,8 @@ def greedy_full(model: OracleModel, prompt, n_new: int, max_seq: Optional[int] =
         logits = model.head(x)[0]
         tokens.append(argmax_lowest(logits))
         margins.append(top2_margin(logits))
-    res = DecodeResult(tokens, margins)
+        second.append(runner_up(logits))
+    res = DecodeResult(tokens, margins, runner_up=second)
     if want_hidden:
         res.hidden = np.concatenate(per_pos, axis=1)
     return res
@@ -111,10 +115,10 @@ def self_speculative(model: OracleModel, prompt, n_new: int, exit_layer: int, d:
     logits = prefill(model, prompt, cache)
     out, margins = [argmax_lowest(logits)], [top2_margin(logits)]
     pos, last = P, out[0]
-    res = DecodeResult(out, margins)
+    res = DecodeResult(out, margins, runner_up=[runner_up(logits)])
     while len(out) < n_new:
         # self-drafting: d early-exit steps; X[i] is the exit state x_E of the i-th row
-        D, dm_, X = [], [], []
+        D, dm_, d2, X = [], [], [], []
         u = last
         for i in range(d):
             x = model.run_layers(model.embed_tokens([u]), [pos + i], cache, 0, E)
@@ -122,6 +126,7 @@ def self_speculative(model: OracleModel, prompt, n_new: int, exit_layer: int, d:
             lg = model.head(x)[0]                       # early exit: g(x_E)
             D.append(argmax_lowest(lg))
             dm_.append(top2_margin(lg))
+            d2.append(runner_up(lg))
             u = D[-1]
         if reuse:
             # the last draft has not been an input yet: early layers only, no head
@@ -135,18 +140,20 @@ def self_speculative(model: OracleModel, prompt, n_new: int, exit_layer: int, d:
         lg = model.head(xl)
         V = [argmax_lowest(lg[i]) for i in range(d + 1)]
         vm = [top2_margin(lg[i]) for i in range(d + 1)]
+        v2 = [runner_up(lg[i]) for i in range(d + 1)]
         # acceptance: longest prefix of drafts equal to the verified tokens
         n = 0
         while n < d and D[n] == V[n]:
             n += 1
         emitted = D[:n] + [V[n]]
         emitted_m = vm[:n + 1]
-        res.rounds.append(RoundTrace(pos, last, D, V, n, dm_, vm))
+        res.rounds.append(RoundTrace(pos, last, D, V, n, dm_, vm, draft_runner_up=d2, verify_runner_up=v2))
         res.drafted += d
         res.accepted += n
         room = n_new - len(out)
         out.extend(emitted[:room])
         margins.extend(emitted_m[:room])
+        res.runner_up.extend(v2[:n + 1][:room])
         pos += n + 1          # crop: positions beyond pos are dead and get overwritten
         last = V[n]
         if round_hook is not None:
@@ -157,7 +164,7 @@ def self_speculative(model: OracleModel, prompt, n_new: int, exit_layer: int, d:
 def self_speculative_dynamic(model: OracleModel, prompt, n_new: int, e_low: int, e_high: int, d: int,
                              tau: float, max_seq: Optional[int] = None) -> DecodeResult:
     """Self-speculative decoding with a per-token exit layer (the extension the paper's closing section
-    names as future work: "dynamic conditions to determine a different exit layer for each token").
+    names as future work: an exit layer chosen per token by a condition evaluated while decoding).
 
     The paper gives no algorithm; the reading taken here keeps everything of Section 4.3 and lets a
     draft leave at one of two layers:

@@ -1,7 +1,8 @@
 """GPU parity at full size: the 1.5B bf16 workload (24 layers, d_model 2048, prompt 512, 256 new
 tokens, E=8, d=6) in the launch configuration bench.py times, against the CPU oracle run on the
 same seeded weights with bf16-rounded activations.  Ids identical except at flagged near-ties
-(oracle margin < 1e-2); teacher-forced argmax of every row; hidden states within 2e-2."""
+(oracle margin < 1e-2, or inside the bf16 noise band with the GPU's id equal to the oracle's
+runner-up: parity_util.excusable_flip); teacher-forced argmax of every row; hidden states within 2e-2."""
 import time
 
 import numpy as np
@@ -9,7 +10,7 @@ import pytest
 
 import oracle as O
 import workloads as W
-from parity_util import same_until_near_tie, rel_err_rows, near_tie_from_either_side, gpu_decisions, NEAR_TIE
+from parity_util import same_until_near_tie, rel_err_rows, excusable_flip, gpu_decisions, NEAR_TIE, MAX_NOISE_FLIPS
 
 pytestmark = pytest.mark.gpu
 
@@ -36,8 +37,8 @@ def test_c2_generate_ids(c2):
     ar, _ = gm.generate(prompt, w.n_new, 0, 0)
     stepped, gpu_margins = gpu_decisions(gm, prompt, w.n_new, w.exit_layer, w.draft_len)
     assert stepped == toks
-    n = same_until_near_tie(toks, ref.tokens, ref.margins, gpu_margins=gpu_margins)
-    same_until_near_tie(ar, ref.tokens, ref.margins, gpu_margins=gpu_margins)
+    n = same_until_near_tie(toks, ref.tokens, ref.margins, runner_up=ref.runner_up, gpu_margins=gpu_margins)
+    same_until_near_tie(ar, ref.tokens, ref.margins, runner_up=ref.runner_up, gpu_margins=gpu_margins)
     print(f"[c2] {n}/{w.n_new} ids compared before a near-tie; gpu acceptance {st.acceptance:.3f}", flush=True)
     assert toks == ar
     assert len(toks) == w.n_new
@@ -53,12 +54,14 @@ def test_c2_teacher_forced_and_hidden_states(c2):
     am, mg = gm.score(seq)
     gm.debug_capture(False)
     firm = [i for i in range(w.n_new) if ref.margins[i] >= NEAR_TIE]
-    bad = [(i, float(ref.margins[i]), float(mg[P - 1 + i])) for i in firm
-           if am[P - 1 + i] != ref.tokens[i] and not near_tie_from_either_side(ref.margins[i], mg[P - 1 + i])]
-    assert not bad, bad   # (position, oracle margin, gpu margin)
     flipped = [i for i in firm if am[P - 1 + i] != ref.tokens[i]]
-    assert len(flipped) <= 3, flipped     # such flips are rare
-    print(f"[c2] ids differing at oracle margin >= 1e-2 while the gpu's own margin is a near-tie: {flipped}", flush=True)
+    bad = [(i, int(am[P - 1 + i]), ref.tokens[i], ref.runner_up[i], float(ref.margins[i]), float(mg[P - 1 + i]))
+           for i in flipped
+           if not excusable_flip(am[P - 1 + i], ref.margins[i], ref.runner_up[i], mg[P - 1 + i], wide=True)]
+    assert not bad, bad   # (position, gpu id, oracle id, oracle runner-up, oracle margin, gpu margin)
+    assert len(flipped) <= MAX_NOISE_FLIPS, flipped     # such flips are rare
+    print(f"[c2] ids differing at oracle margin in [1e-2, 2.5e-2) where the gpu chose the oracle's runner-up: "
+          f"{[(i, round(float(ref.margins[i]), 4)) for i in flipped]}", flush=True)
     assert len(firm) >= int(0.8 * w.n_new)
     # hidden states of every layer at every position, from one oracle pass over the same sequence
     hid = []
@@ -90,12 +93,13 @@ def test_c2_round_replay(c2):
         gm.verify(E, d)
         D, V, dmarg, _, n_acc = gm.peek_round(d)
         kd = next((i for i, g in enumerate(r.draft_margins) if g < NEAR_TIE), d)
-        # bf16 rounding noise moves a margin by up to ~1e-2 at this width (pinned on the CPU in
-        # test_oracle_invariants): a draft that differs where the oracle's margin is just above the
-        # threshold and the GPU's own margin is below it is a near-tie seen from the other side
+        # bf16 rounding noise moves a margin by up to ~1.5e-2 at this width (pinned on the CPU in
+        # test_oracle_invariants): a draft may differ where the oracle's margin is inside that band AND
+        # the GPU drafted the oracle's runner-up AND the GPU's own margin is a near-tie
         kg = next((i for i in range(kd) if D[i] != r.draft[i]), kd)
         if kg < kd:
-            assert r.draft_margins[kg] < 2.5 * NEAR_TIE and dmarg[kg] < NEAR_TIE, (kg, r.draft_margins, dmarg)
+            assert excusable_flip(D[kg], r.draft_margins[kg], r.draft_runner_up[kg], dmarg[kg], wide=True), \
+                (kg, D, r.draft, r.draft_runner_up, r.draft_margins, dmarg)
             gpu_side_ties += 1
             kd = kg
         assert D[:kd] == r.draft[:kd]

@@ -104,6 +104,17 @@ def test_argmax_takes_lowest_index_on_ties_and_margin():
     assert abs(O.top2_margin(np.array([0.1, 0.9, 0.7])) - 0.2) < 1e-12
 
 
+def test_runner_up_is_the_second_entry_of_a_stable_sort():
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        lg = rng.integers(0, 6, size=12).astype(np.float32)      # many exact ties
+        order = sorted(range(len(lg)), key=lambda i: (-lg[i], i))  # by value, lowest index first
+        assert O.argmax_lowest(lg) == order[0]
+        assert O.runner_up(lg) == order[1]
+        assert abs(O.top2_margin(lg) - (lg[order[0]] - lg[order[1]])) < 1e-12
+    assert O.runner_up(np.array([0.1, 0.9, 0.7])) == 2
+
+
 # ------------------------------------------------------------------ one layer, special cases
 def _tiny_cfg(**kw):
     base = dict(name="t", n_layers=1, d_model=8, n_q_heads=2, n_kv_heads=2, head_dim=4,
