@@ -217,6 +217,23 @@ int ls_set_exchange(ls_ctx *ctx, int32_t max_tagged_rows);
  * Returns LS_OK, LS_E_ARG for a null context or LS_E_RANGE for any other value. */
 int ls_set_prompt_tiles(ls_ctx *ctx, int32_t rows);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture set-up, tight serving
+ * loops, harnesses that forbid hipMalloc): ls_generate without a caller workspace and without a
+ * context.  The KV cache and every per-stage buffer live in a fixed array inside the library
+ * (ls_static_workspace_limit() bytes, 8 MiB, held by every GPU the library runs on until the process
+ * ends), so the call allocates no device memory at all; it serves models whose
+ * ls_workspace_bytes(cfg) fits that array (tiny models) and returns LS_E_CAPACITY, before touching
+ * the device, for any other.  cfg / weights as for ls_load_weights (DEVICE weight pointers, kept only
+ * for the duration of the call), the remaining arguments and the results as for ls_generate.
+ * The array keeps the previous call's contents; every call rebuilds the tables, counters and state
+ * it needs, so successive calls with different configurations are independent.  All calls on one
+ * GPU share the one array: calls that overlap in time on the same GPU race and give undefined
+ * results (serialise them; calls on different GPUs do not interact).  Synchronises `stream`. */
+int ls_generate_static(const ls_config *cfg, const ls_weights *weights, const int32_t *dev_prompt,
+                       int32_t n_prompt, int32_t max_new, int32_t exit_layer, int32_t d, int32_t eos_id,
+                       int32_t *dev_out_tokens, ls_stats *host_stats, void *stream);
+size_t ls_static_workspace_limit(void);
+
 const char *ls_strerror(int code);
 
 /* Frees the host object only; the workspace and the weights stay with the caller. */

@@ -5,5 +5,5 @@ The work is done by hand-written HIP kernels behind the C ABI in include/ls.h
 arguments: torch provides device memory and streams, nothing else.
 """
 from .binding import (  # noqa: F401
-    LsError, LsModel, Stats, lib, lib_path, config_struct, LS_F32, LS_BF16,
+    LsError, LsModel, Stats, DeviceWeights, generate_static, lib, lib_path, config_struct, LS_F32, LS_BF16,
 )

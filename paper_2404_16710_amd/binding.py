@@ -20,6 +20,7 @@ EXPORTS = (
     "ls_workspace_bytes", "ls_load_weights", "ls_prefill", "ls_draft", "ls_verify", "ls_generate",
     "ls_generate_no_reuse", "ls_generate_dynamic", "ls_generate_early_exit", "ls_score", "ls_probe_layers", "ls_get_state", "ls_peek_round", "ls_debug_capture",
     "ls_debug_timeline", "ls_debug_copy", "ls_set_launch", "ls_set_exchange", "ls_set_prompt_tiles", "ls_debug_spin_limit", "ls_strerror", "ls_destroy",
+    "ls_generate_static", "ls_static_workspace_limit",
 )
 
 
@@ -121,6 +122,11 @@ def lib() -> C.CDLL:
     L.ls_set_prompt_tiles.argtypes = [vp, i32]
     L.ls_debug_spin_limit.restype = C.c_int
     L.ls_debug_spin_limit.argtypes = [vp, i32]
+    L.ls_generate_static.restype = C.c_int
+    L.ls_generate_static.argtypes = [C.POINTER(ls_config), C.POINTER(ls_weights), vp, i32, i32, i32, i32, i32, vp,
+                                     C.POINTER(ls_stats), vp]
+    L.ls_static_workspace_limit.restype = C.c_size_t
+    L.ls_static_workspace_limit.argtypes = []
     L.ls_strerror.restype = C.c_char_p
     L.ls_strerror.argtypes = [C.c_int]
     L.ls_destroy.restype = None
@@ -142,6 +148,66 @@ def _check(code: int, what: str) -> None:
         raise LsError(code, what)
 
 
+class DeviceWeights:
+    """The tensors of a model on the GPU (torch owns the memory) and the ls_weights struct that
+    points at them.  weights: dict as produced by workloads.make_weights."""
+
+    def __init__(self, model_cfg, weights: dict, device):
+        import torch
+        self.tensors = []   # keeps device memory alive
+        self.by_name = {}   # (name, layer) -> tensor; layer -1 for the global tensors
+
+        def up(a: np.ndarray):
+            if a.dtype == np.uint16:
+                t = torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+            else:
+                t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+            self.tensors.append(t)
+            return t.data_ptr()
+
+        L = model_cfg.n_layers
+        w = ls_weights()
+        for name in ("embed", "final_norm", "lm_head"):
+            setattr(w, name, up(weights[name]))
+            self.by_name[(name, -1)] = self.tensors[-1]
+        self.ptr_arrays = {}
+        for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "attn_norm", "ffn_norm"):
+            ptrs = []
+            for l in range(L):
+                ptrs.append(up(weights["layers"][l][name]))
+                self.by_name[(name, l)] = self.tensors[-1]
+            arr = (C.c_void_p * L)(*ptrs)
+            self.ptr_arrays[name] = arr
+            setattr(w, name, C.cast(arr, _PP))
+        self.struct = w
+
+    def replace(self, name: str, layer: int, a: np.ndarray) -> None:
+        """Overwrites one tensor in place (same shape and dtype): the device address stays valid."""
+        import torch
+        t = self.by_name[(name, layer)]
+        src = torch.from_numpy(a.view(np.int16)).view(torch.bfloat16) if a.dtype == np.uint16 else torch.from_numpy(a)
+        assert src.shape == t.shape and src.dtype == t.dtype
+        t.copy_(src)
+
+
+def generate_static(model_cfg, dev_weights: DeviceWeights, max_seq: int, prompt: Sequence[int], max_new: int,
+                    exit_layer: int, d: int, eos_id: int = -1, max_draft: int = 15, device: str = "cuda:0"):
+    """ls_generate_static: the whole job with the library's own fixed workspace (no context, no
+    caller workspace).  Returns (tokens, stats) like LsModel.generate."""
+    import torch
+    cfg_c = config_struct(model_cfg, max_seq, max_draft)
+    dev = torch.device(device)
+    p = torch.as_tensor(np.asarray(prompt, dtype=np.int32), device=dev)
+    out = torch.empty(max_new, dtype=torch.int32, device=dev)
+    st = ls_stats()
+    stream = C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+    _check(lib().ls_generate_static(C.byref(cfg_c), C.byref(dev_weights.struct), C.c_void_p(p.data_ptr()), len(prompt),
+                                    max_new, exit_layer, d, eos_id, C.c_void_p(out.data_ptr()), C.byref(st), stream),
+           "ls_generate_static")
+    stats = Stats(st.rounds, st.drafted, st.accepted, st.generated, st.ms_prefill, st.ms_decode)
+    return out.cpu().numpy()[: stats.generated].tolist(), stats
+
+
 class LsModel:
     """One model + one sequence on the current CUDA(HIP) device.
 
@@ -159,27 +225,9 @@ class LsModel:
         self.cfg = model_cfg
         self.max_seq, self.max_draft = int(max_seq), int(max_draft)
         self._cfg_c = config_struct(model_cfg, max_seq, max_draft)
-        self._tensors = []   # keeps device memory alive
-
-        def up(a: np.ndarray):
-            if a.dtype == np.uint16:
-                t = torch.from_numpy(a.view(np.int16)).to(self.device).view(torch.bfloat16)
-            else:
-                t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.device)
-            self._tensors.append(t)
-            return t.data_ptr()
-
-        L = model_cfg.n_layers
-        w = ls_weights()
-        w.embed = up(weights["embed"])
-        w.final_norm = up(weights["final_norm"])
-        w.lm_head = up(weights["lm_head"])
-        self._ptr_arrays = {}
-        for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "attn_norm", "ffn_norm"):
-            arr = (C.c_void_p * L)(*[up(weights["layers"][l][name]) for l in range(L)])
-            self._ptr_arrays[name] = arr
-            setattr(w, name, C.cast(arr, _PP))
-        self._w = w
+        self._dev_weights = DeviceWeights(model_cfg, weights, self.device)
+        self._tensors = self._dev_weights.tensors
+        w = self._w = self._dev_weights.struct
         nbytes = self.lib.ls_workspace_bytes(C.byref(self._cfg_c))
         if nbytes == 0:
             raise LsError(-1, "ls_workspace_bytes")
@@ -199,6 +247,12 @@ class LsModel:
     def _dev_i32(self, ids: Sequence[int]):
         t = self.torch.as_tensor(np.asarray(ids, dtype=np.int32), device=self.device)
         return t
+
+    def replace_tensor(self, name: str, layer: int, a: np.ndarray) -> None:
+        """New values for one weight tensor (same shape); no call may be in flight."""
+        self.torch.cuda.synchronize(self.device)
+        self._dev_weights.replace(name, layer, a)
+        self.torch.cuda.synchronize(self.device)
 
     def close(self):
         if getattr(self, "ctx", None):

@@ -19,6 +19,7 @@ extern "C" int ls_kernel_setup(int dtype_is_bf16, int hd, int* max_blocks_per_cu
 extern "C" int ls_launch_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
 extern "C" int ls_prefill_layers(const LsPfParams* p, const LsLayerW* host_layers, int pos0, int M, hipStream_t s);
 extern "C" int ls_prefill_finish(const LsPfParams* p, int last_row, hipStream_t s);
+extern "C" int ls_static_scratch_ptr(void** ptr);
 
 namespace {
 
@@ -104,6 +105,7 @@ struct ls_ctx {
   int draft_E, draft_d;
   int pos_bound;    // upper bound of the device-side position, for capacity checks
   hipEvent_t ev[3];
+  bool owns_events;
   float* capture;
   unsigned long long* prof;
   int prof_cap, prof_wg;
@@ -187,10 +189,11 @@ size_t ls_workspace_bytes(const ls_config* cfg) {
   return make_layout(cfg).total;
 }
 
-int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspace, size_t workspace_bytes,
-                    ls_ctx** out) {
-  if (!out) return LS_E_ARG;
-  *out = nullptr;
+// Validates the configuration, the weight pointers and the workspace, then fills *c: uploads the
+// layer pointer table and the rotary table into the workspace and zeroes counters and state.
+// `events`: three timing events the context uses but does not own, or null to create its own.
+static int init_ctx(ls_ctx* c, const ls_config* cfg, const ls_weights* w, void* dev_workspace, size_t workspace_bytes,
+                    const hipEvent_t* events) {
   if (!config_ok(cfg) || !w || !dev_workspace) return LS_E_ARG;
   if ((uintptr_t)dev_workspace % 256) return LS_E_ARG;
   if (!w->embed || !w->final_norm || !w->lm_head || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate || !w->w_up ||
@@ -205,8 +208,6 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   const Layout lay = make_layout(cfg);
   if (workspace_bytes < lay.total) return LS_E_CAPACITY;
 
-  ls_ctx* c = new (std::nothrow) ls_ctx();
-  if (!c) return LS_E_ARG;
   c->cfg = *cfg;
   c->lay = lay;
   c->ws = static_cast<char*>(dev_workspace);
@@ -218,10 +219,10 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
 
   hipDeviceProp_t prop;
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) { delete c; return LS_E_HIP; }
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return LS_E_HIP;
   c->n_cu = prop.multiProcessorCount;
   int nb = 0;
-  if (ls_kernel_setup(cfg->dtype == LS_BF16, cfg->head_dim, &nb) != 0 || nb < 1) { delete c; return LS_E_HIP; }
+  if (ls_kernel_setup(cfg->dtype == LS_BF16, cfg->head_dim, &nb) != 0 || nb < 1) return LS_E_HIP;
   c->max_wg_per_cu = nb > 2 ? 2 : nb;
   c->wg_per_cu = c->max_wg_per_cu;
   c->grid = c->n_cu * c->wg_per_cu;
@@ -247,8 +248,12 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   okc = okc && hipMemcpy(c->ws + lay.rope_sin, sn.data(), sizeof(float) * sn.size(), hipMemcpyHostToDevice) == hipSuccess;
   okc = okc && hipMemset(c->ws + lay.xbuf, 0, lay.x_pf - lay.xbuf) == hipSuccess;
   okc = okc && hipDeviceSynchronize() == hipSuccess;
-  for (int i = 0; i < 3 && okc; ++i) okc = hipEventCreate(&c->ev[i]) == hipSuccess;
-  if (!okc) { delete c; return LS_E_HIP; }
+  c->owns_events = events == nullptr;
+  for (int i = 0; i < 3 && okc; ++i) {
+    if (events) c->ev[i] = events[i];
+    else okc = hipEventCreate(&c->ev[i]) == hipSuccess;
+  }
+  if (!okc) return LS_E_HIP;
 
   LsKParams& p = c->base;
   memset(&p, 0, sizeof(p));
@@ -288,6 +293,17 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   f.x_pf = reinterpret_cast<float*>(c->ws + lay.x_pf); f.a_pf = c->ws + lay.a_pf; f.q_pf = c->ws + lay.q_pf;
   f.o_pf = c->ws + lay.o_pf; f.act_pf = c->ws + lay.act_pf; f.xbuf = p.xbuf; f.ssq = p.ssq;
   c->gemm_prefill = true;
+  return LS_OK;
+}
+
+int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspace, size_t workspace_bytes,
+                    ls_ctx** out) {
+  if (!out) return LS_E_ARG;
+  *out = nullptr;
+  ls_ctx* c = new (std::nothrow) ls_ctx();
+  if (!c) return LS_E_ARG;
+  const int rc = init_ctx(c, cfg, w, dev_workspace, workspace_bytes, nullptr);
+  if (rc != LS_OK) { delete c; return rc; }
   *out = c;
   return LS_OK;
 }
@@ -553,8 +569,41 @@ const char* ls_strerror(int code) {
 
 void ls_destroy(ls_ctx* c) {
   if (!c) return;
-  for (int i = 0; i < 3; ++i) (void)hipEventDestroy(c->ev[i]);
+  if (c->owns_events)
+    for (int i = 0; i < 3; ++i) (void)hipEventDestroy(c->ev[i]);
   delete c;
+}
+
+size_t ls_static_workspace_limit(void) { return LS_STATIC_SCRATCH_BYTES; }
+
+int ls_generate_static(const ls_config* cfg, const ls_weights* w, const int32_t* dev_prompt, int32_t n_prompt,
+                       int32_t max_new, int32_t E, int32_t d, int32_t eos, int32_t* dev_out, ls_stats* stats,
+                       void* stream) {
+  if (!config_ok(cfg)) return LS_E_ARG;
+  // sizes beyond the fixed array are refused before anything touches the device
+  if (make_layout(cfg).total > (size_t)LS_STATIC_SCRATCH_BYTES) return LS_E_CAPACITY;
+  // set-up, once per device with that device current: the address of this device's copy of the array
+  // (never the array's name: in host code that is not a device address) and the timing events
+  constexpr int kMaxDev = 64;
+  struct PerDevice { hipEvent_t ev[3]; bool ready; };
+  static PerDevice per_dev[kMaxDev];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return LS_E_HIP;
+  void* scratch = nullptr;
+  if (ls_static_scratch_ptr(&scratch) != 0) return LS_E_HIP;
+  PerDevice& pd = per_dev[dev];
+  if (!pd.ready) {
+    for (int i = 0; i < 3; ++i)
+      if (hipEventCreate(&pd.ev[i]) != hipSuccess) return LS_E_HIP;
+    pd.ready = true;
+  }
+  // The array keeps the previous call's contents: init_ctx uploads the tables again and zeroes every
+  // counter, flag and state word of this configuration's layout; stale cache rows and stage buffers are
+  // overwritten before they are read.
+  ls_ctx c{};
+  int rc = init_ctx(&c, cfg, w, scratch, LS_STATIC_SCRATCH_BYTES, pd.ev);
+  if (rc != LS_OK) return rc;
+  return generate_impl(&c, dev_prompt, n_prompt, max_new, E, d, eos, cfg->n_layers, dev_out, stats, stream);
 }
 
 }  // extern "C"

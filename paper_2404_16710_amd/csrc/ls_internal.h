@@ -15,6 +15,9 @@
 #define LS_RED_BYTES 8192        // LDS bytes for the cross-wave reduction of accumulator tiles
 #define LS_SMEM_BYTES (LS_ACT_BYTES + LS_RED_BYTES + LS_MISC_BYTES)
 
+// Size of the library's own workspace array (ls_generate_static): enough for tiny models only.
+#define LS_STATIC_SCRATCH_BYTES (8u << 20)
+
 struct LsLayerW {
   const void *wq, *wk, *wv, *wo, *wg, *wu, *wd, *attn_norm, *ffn_norm;
 };

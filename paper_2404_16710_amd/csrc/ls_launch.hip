@@ -24,6 +24,26 @@ extern "C" int ls_launch_copy(const void* src, void* dst, size_t bytes, hipStrea
   return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
+// Workspace of ls_generate_static: callers that may not allocate device memory get the KV cache and all
+// per-stage scratch from this fixed array instead of a buffer of their own.  Every GPU the library runs
+// on holds its own copy at its own address; host code never uses the array's name as an address, only
+// the pointer hipGetSymbolAddress returns for the current device, looked up once per device.
+static __device__ __align__(256) unsigned char ls_static_scratch[LS_STATIC_SCRATCH_BYTES];
+
+extern "C" int ls_static_scratch_ptr(void** ptr) {
+  constexpr int kMaxDev = 64;
+  static void* dev_ptr[kMaxDev];   // zero-initialised: not looked up yet
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return 1;
+  void* p = __atomic_load_n(&dev_ptr[dev], __ATOMIC_ACQUIRE);
+  if (p == nullptr) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(ls_static_scratch)) != hipSuccess || p == nullptr) return 1;
+    __atomic_store_n(&dev_ptr[dev], p, __ATOMIC_RELEASE);   // every thread finds the same address
+  }
+  *ptr = p;
+  return 0;
+}
+
 enum { LS_K_PROMPT = 0, LS_K_DECODE, LS_K_GREEDY, LS_K_STEP, LS_K_AUX, LS_K_COUNT };
 
 static const void* kernel_symbol(int which, int dtype_is_bf16, int hd) {

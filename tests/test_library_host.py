@@ -73,6 +73,24 @@ def test_null_and_misaligned_arguments_are_rejected_without_a_gpu():
     lib.ls_destroy(None)                                     # harmless
 
 
+def test_static_workspace_variant_rejects_what_does_not_fit_before_touching_the_device():
+    lib = B.lib()
+    limit = lib.ls_static_workspace_limit()
+    assert limit == 8 << 20
+    w = B.ls_weights()
+    st = B.ls_stats()
+    small = B.config_struct(W.get_workload("c1").model, 113)
+    assert 0 < lib.ls_workspace_bytes(C.byref(small)) <= limit
+    big = B.config_struct(W.get_workload("c2").model, 785)
+    assert lib.ls_workspace_bytes(C.byref(big)) > limit
+    args = (None, 4, 4, 1, 1, -1, None, C.byref(st), None)
+    assert lib.ls_generate_static(C.byref(big), C.byref(w), *args) == -3      # LS_E_CAPACITY
+    bad = B.config_struct(W.get_workload("c1").model, 113)
+    bad.head_dim = 96
+    assert lib.ls_generate_static(C.byref(bad), C.byref(w), *args) == -1      # LS_E_ARG
+    assert lib.ls_generate_static(None, C.byref(w), *args) == -1
+
+
 def test_binding_refuses_to_run_without_a_gpu():
     import torch
     if torch.cuda.is_available():
