@@ -9,6 +9,7 @@ from .synth import (  # noqa: F401
     CONFIGS,
     get_workload,
     make_weights,
+    make_tensor,
     make_prompt,
     WEIGHT_NAMES_PER_LAYER,
     shrink,

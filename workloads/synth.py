@@ -201,6 +201,17 @@ def make_weights(w: Workload, exit_layer: Optional[int] = None, threads: int = 8
     return out
 
 
+def make_tensor(w: Workload, name: str, layer: int, exit_layer: Optional[int] = None) -> np.ndarray:
+    """One tensor of the model, exactly as make_weights fills it (layer -1 for the global tensors).
+    A sweep over exit layers only has to replace wo / w_down of the layers whose scaling changes."""
+    e = w.exit_layer if exit_layer is None else exit_layer
+    m = w.model
+    a = np.empty(_tensor_shapes(m)[name], dtype=np.uint16 if m.dtype == "bf16" else np.float32)
+    for blk, (r0, r1) in enumerate(_row_blocks(a.shape)):
+        _fill_block(w, name, layer, e, a, blk, r0, r1)
+    return a
+
+
 def make_prompt(w: Workload, n_prompt: Optional[int] = None) -> np.ndarray:
     """Prompt ids, uniform in [0, vocab), int32."""
     n = w.n_prompt if n_prompt is None else n_prompt
