@@ -201,14 +201,6 @@ int ls_debug_spin_limit(ls_ctx *ctx, int32_t polls);
  * Returns the number of workgroups a launch will use, or a negative error. */
 int ls_set_launch(ls_ctx *ctx, int32_t workgroups_per_cu);
 
-/* How workgroups hand a pass's rows to each other between stages.  Passes of the decoding calls
- * (ls_draft, ls_verify, ls_generate, ls_generate_early_exit) with at most max_tagged_rows rows
- * publish every 32-bit value together with a stage tag and poll for the tags they need; passes with
- * more rows, and all prompt passes, separate their stages with a grid-wide barrier.  Both give the
- * same bits.  0 (the default) selects barriers everywhere, 16 tags everywhere.  A pending ls_draft
- * result is discarded.  Returns LS_OK or a negative error. */
-int ls_set_exchange(ls_ctx *ctx, int32_t max_tagged_rows);
-
 /* Shape of the prompt pass used by later calls.  Prompts of 32 or more ids run as GEMMs over all
  * rows of a chunk, with output tiles of 128, 64 or 32 rows chosen from the number of tiles the
  * launch would have (rows = 0, the default); 32, 64 or 128 force that tile height, 16 sends every

@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 EXPORTS = (
     "ls_workspace_bytes", "ls_load_weights", "ls_prefill", "ls_draft", "ls_verify", "ls_generate",
     "ls_generate_no_reuse", "ls_generate_dynamic", "ls_generate_early_exit", "ls_score", "ls_probe_layers", "ls_get_state", "ls_peek_round", "ls_debug_capture",
-    "ls_debug_timeline", "ls_debug_copy", "ls_set_launch", "ls_set_exchange", "ls_set_prompt_tiles", "ls_debug_spin_limit", "ls_strerror", "ls_destroy",
+    "ls_debug_timeline", "ls_debug_copy", "ls_set_launch", "ls_set_prompt_tiles", "ls_debug_spin_limit", "ls_strerror", "ls_destroy",
     "ls_generate_static", "ls_static_workspace_limit",
 )
 
@@ -116,8 +116,6 @@ def lib() -> C.CDLL:
     L.ls_debug_copy.argtypes = [vp, vp, C.c_size_t, vp]
     L.ls_set_launch.restype = C.c_int
     L.ls_set_launch.argtypes = [vp, i32]
-    L.ls_set_exchange.restype = C.c_int
-    L.ls_set_exchange.argtypes = [vp, i32]
     L.ls_set_prompt_tiles.restype = C.c_int
     L.ls_set_prompt_tiles.argtypes = [vp, i32]
     L.ls_debug_spin_limit.restype = C.c_int
@@ -275,9 +273,6 @@ class LsModel:
 
     def debug_spin_limit(self, polls: int) -> None:
         _check(self.lib.ls_debug_spin_limit(self.ctx, polls), "ls_debug_spin_limit")
-
-    def set_exchange(self, max_tagged_rows: int) -> None:
-        _check(self.lib.ls_set_exchange(self.ctx, max_tagged_rows), "ls_set_exchange")
 
     def set_prompt_tiles(self, rows: int) -> None:
         _check(self.lib.ls_set_prompt_tiles(self.ctx, rows), "ls_set_prompt_tiles")

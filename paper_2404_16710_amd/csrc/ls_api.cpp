@@ -25,7 +25,7 @@ namespace {
 
 struct Layout {
   size_t layers, rope_cos, rope_sin, kcache, vcache, xbuf, ssq, qbuf, obuf, actbuf, attn_part, attn_cnt, cand, bar,
-      state, xt, sst, qt, ot, kt, vt, at, ct, attn_cnt_ll, x_pf, a_pf, q_pf, o_pf, act_pf, total;
+      state, x_pf, a_pf, q_pf, o_pf, act_pf, total;
   int pf_rows;
 };
 
@@ -63,7 +63,7 @@ Layout make_layout(const ls_config* c) {
   L.kcache = take(esz * c->n_layers * kvd * c->max_seq);
   L.vcache = take(esz * c->n_layers * kvd * c->max_seq);
   L.xbuf = take(sizeof(float) * LS_ROWS * c->d_model);
-  L.ssq = take(sizeof(float) * LS_ROWS * (c->d_model / 8));   // per-tile sums of squares, tiles of 8 rows or more
+  L.ssq = take(sizeof(float) * LS_ROWS * kMaxGrid);           // sums of squares of the rows, one per workgroup
   L.qbuf = take(esz * LS_ROWS * qd);
   L.obuf = take(esz * LS_ROWS * qd);
   L.actbuf = take(esz * LS_ROWS * c->ffn_dim);
@@ -72,16 +72,6 @@ Layout make_layout(const ls_config* c) {
   L.cand = take(sizeof(float) * 4 * LS_ROWS * kMaxGrid);
   L.bar = take(4096);
   L.state = take(sizeof(LsState));
-  // tagged exchange: 8 bytes per 32-bit payload
-  L.xt = take(8 * (size_t)LS_ROWS * c->d_model);
-  L.sst = take(8 * (size_t)LS_ROWS * (c->d_model / 8));
-  L.qt = take(8 * (size_t)LS_ROWS * qd * esz / 4);
-  L.ot = take(8 * (size_t)LS_ROWS * qd * esz / 4);
-  L.kt = take(8 * (size_t)LS_ROWS * kvd * esz / 4);
-  L.vt = take(8 * (size_t)LS_ROWS * kvd * esz / 4);
-  L.at = take(8 * (size_t)LS_ROWS * c->ffn_dim * esz / 4);
-  L.ct = take(8 * (size_t)2 * kMaxGrid * LS_ROWS * 4);
-  L.attn_cnt_ll = take(sizeof(uint32_t) * c->n_kv_heads);
   L.pf_rows = c->max_seq < kPrefillRows ? c->max_seq : kPrefillRows;
   L.x_pf = take(sizeof(float) * L.pf_rows * c->d_model);
   L.a_pf = take(esz * L.pf_rows * c->d_model);
@@ -116,29 +106,18 @@ struct ls_ctx {
 
 namespace {
 
-// Rows per weight tile (8, 12 or 16) for a matrix with `rows` output rows spread over `grid`
-// workgroups in whole tiles.  A workgroup's time in the stage is about (tiles it gets) x (rows per
-// tile + 4): a tile with fewer rows streams proportionally less, but every tile pays a fixed part
-// (its share of the loads in flight is filled with repeated rows, and each tile has an epilogue).
-// Measured: 16 rows for ffn 11008 / 13824 / 14336 on 256 workgroups, 12 for ffn 5632.
-int choose_tile_rows(int rows, int grid) {
-  int best = 16, best_cost = INT32_MAX;
-  for (int gs = 16; gs >= 8; gs -= 4) {
-    const int tiles = (rows + gs - 1) / gs;
-    const int cost = (tiles + grid - 1) / grid * (gs + 4);
-    if (cost < best_cost) { best_cost = cost; best = gs; }
-  }
-  return best;
-}
-
 void set_decomposition(ls_ctx* c) {
   const ls_config& g = c->cfg;
-  // O / down projections: smaller tiles only when some workgroup would otherwise get two (more
-  // workgroups with a tile means more readers of the broadcast input rows, which costs as much as
-  // the shorter weight stream gains)
-  c->base.gs_x = g.d_model / 16 <= c->grid ? 16 : choose_tile_rows(g.d_model, c->grid);
-  c->base.gs_ffn = choose_tile_rows(g.ffn_dim, c->grid);
-  c->base.ssq_nt = (g.d_model + c->base.gs_x - 1) / c->base.gs_x;
+  // Every matrix product splits its output rows evenly over the workgroups in units of four (the
+  // kernel's part_of); here only what the kernel needs up front: one sum-of-squares slot per
+  // workgroup and residual row, and the most 16-row tiles a workgroup gets in the O / down
+  // projections (at least four units per active workgroup there).
+  c->base.ssq_nt = c->grid;
+  const int units = g.d_model / 4;
+  int nwg = units / 4;
+  nwg = nwg < 1 ? 1 : (nwg > c->grid ? c->grid : nwg);
+  const int most_units = (units + nwg - 1) / nwg;
+  c->base.x_tiles = (most_units + 3) / 4;
   // attention work items: (kv head, C consecutive 64-position tiles), C the smallest count for
   // which a full cache gives at most one item per workgroup
   const int max_tiles = (g.max_seq + LS_ATTN_TILE - 1) / LS_ATTN_TILE;
@@ -174,7 +153,7 @@ int read_state(ls_ctx* c, LsState* st, hipStream_t s) {
 // (counters, state and tagged buffers are contiguous in the workspace).
 int recover(ls_ctx* c, hipStream_t s) {
   if (!c->poisoned) return LS_OK;
-  if (hipMemsetAsync(c->ws + c->lay.attn_cnt, 0, c->lay.x_pf - c->lay.attn_cnt, s) != hipSuccess) return LS_E_HIP;
+  if (hipMemsetAsync(c->ws + c->lay.xbuf, 0, c->lay.x_pf - c->lay.xbuf, s) != hipSuccess) return LS_E_HIP;
   c->poisoned = false;
   c->prefilled = c->drafted = false;
   return LS_OK;
@@ -276,12 +255,6 @@ static int init_ctx(ls_ctx* c, const ls_config* cfg, const ls_weights* w, void* 
   p.cand = reinterpret_cast<float*>(c->ws + lay.cand);
   p.bar = reinterpret_cast<uint32_t*>(c->ws + lay.bar);
   p.state = reinterpret_cast<LsState*>(c->ws + lay.state);
-  p.xt = reinterpret_cast<uint64_t*>(c->ws + lay.xt); p.sst = reinterpret_cast<uint64_t*>(c->ws + lay.sst);
-  p.qt = reinterpret_cast<uint64_t*>(c->ws + lay.qt); p.ot = reinterpret_cast<uint64_t*>(c->ws + lay.ot);
-  p.kt = reinterpret_cast<uint64_t*>(c->ws + lay.kt); p.vt = reinterpret_cast<uint64_t*>(c->ws + lay.vt);
-  p.at = reinterpret_cast<uint64_t*>(c->ws + lay.at); p.ct = reinterpret_cast<uint64_t*>(c->ws + lay.ct);
-  p.attn_cnt_ll = reinterpret_cast<uint32_t*>(c->ws + lay.attn_cnt_ll);
-  p.ll_max_rows = 0;
   p.spin_limit = 1 << 22;
   set_decomposition(c);
   c->host_layers = lw;
@@ -305,14 +278,6 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
   const int rc = init_ctx(c, cfg, w, dev_workspace, workspace_bytes, nullptr);
   if (rc != LS_OK) { delete c; return rc; }
   *out = c;
-  return LS_OK;
-}
-
-int ls_set_exchange(ls_ctx* c, int32_t max_tagged_rows) {
-  if (!c) return LS_E_ARG;
-  if (max_tagged_rows < 0 || max_tagged_rows > LS_ROWS) return LS_E_RANGE;
-  c->base.ll_max_rows = max_tagged_rows;
-  c->drafted = false;   // exit states of a pending draft may be in the other representation
   return LS_OK;
 }
 
@@ -352,7 +317,7 @@ static int enqueue_prefill(ls_ctx* c, const int32_t* dev_prompt, int32_t n_promp
     return launch(c, p, s);
   }
   LsPfParams f = c->pf;
-  f.gs_x = c->base.gs_x;
+  f.ssq_nt = c->base.ssq_nt;
   f.tokens = dev_prompt; f.layers_used = layers_used; f.capture = c->capture;
   int last_rows = 0;
   for (int pos0 = 0; pos0 < n_prompt; pos0 += c->lay.pf_rows) {

@@ -22,14 +22,6 @@ struct LsLayerW {
   const void *wq, *wk, *wv, *wo, *wg, *wu, *wd, *attn_norm, *ffn_norm;
 };
 
-// Bookkeeping of the tagged exchange (see ls_kernels.inc); survives prefills and launches.
-struct LsExch {
-  uint32_t seq;             // tag of the most recent stage that published tagged data
-  uint32_t attn_base;       // completed attention items per kv head so far (monotone counters)
-  uint32_t cand_par;        // which of the two candidate buffers the next head stage writes
-  uint32_t xtag[LS_ROWS];   // tag of the current contents of each tagged residual row (0: none)
-};
-
 // Decoding state.  One copy lives in device memory (read by the host through ls_get_state /
 // ls_peek_round); every workgroup keeps an identical working copy in LDS while a program runs.
 struct LsState {
@@ -48,7 +40,6 @@ struct LsState {
   int32_t V[LS_ROWS];
   float dmargin[LS_ROWS];
   float vmargin[LS_ROWS];
-  LsExch ex;
 };
 
 enum LsProgramKind {
@@ -70,7 +61,7 @@ struct LsKParams {
   // workspace
   void *kcache, *vcache;            // [L][nkv][max_seq][hd]
   float *xbuf;                      // [16][dm]  residual rows = exit-state rows
-  float *ssq;                       // [16][ssq_nt] sum of squares of xbuf rows, per gs_x-wide tile
+  float *ssq;                       // [16][ssq_nt] sum of squares of xbuf rows, one slot per workgroup
   void *qbuf, *obuf, *actbuf;       // [16][qd], [16][qd], [16][ffn]
   float *attn_part;                 // [nkv][max_tiles][64][hd+2]
   uint32_t *attn_cnt;               // [nkv]
@@ -80,10 +71,9 @@ struct LsKParams {
   uint32_t *bar;                    // grid barrier counter
   LsState *state;
   float *capture;                   // [L][max_seq][dm] or null
-  // decomposition: output rows per weight tile in the O / down projections (gs_x) and in the
-  // gate / up projections (gs_ffn): 8, 12 or 16, chosen so that the workgroup with the most rows
-  // has as few as possible; ssq_nt = ceil(dm / gs_x) sums of squares per residual row
-  int32_t gs_x, gs_ffn, ssq_nt;
+  // ssq_nt: sums of squares per residual row (the number of workgroups); x_tiles: most weight tiles
+  // a workgroup gets in the O / down projections (two of them share the staged input)
+  int32_t ssq_nt, x_tiles;
   // program
   int32_t kind, E, d, max_new, eos, n_tokens, layers_used;
   int32_t probe;      // LS_PROG_SCORE: argmax of the head after every layer, outputs [layer][row]
@@ -95,16 +85,6 @@ struct LsKParams {
   int32_t *out_tokens;
   float *out_margin;
   int32_t spin_limit;
-  // tagged exchange: 8-byte words (32-bit payload, 32-bit tag) that consumers poll instead of
-  // waiting at a grid barrier; used by passes of at most ll_max_rows rows
-  uint64_t *xt;                     // [16][dm]      residual rows, fp32 payload
-  uint64_t *sst;                    // [16][ssq_nt]  their per-tile sums of squares
-  uint64_t *qt, *ot;                // [16][qd*esz/4]  q rows / attention output rows (model dtype, packed)
-  uint64_t *kt, *vt;                // [16][kvd*esz/4] k and v rows of the pass
-  uint64_t *at;                     // [16][ffn*esz/4] SwiGLU rows
-  uint64_t *ct;                     // [2][grid][16][4] argmax candidates, two buffers used alternately
-  uint32_t *attn_cnt_ll;            // [nkv] monotone completion counters
-  int32_t ll_max_rows;
   // optional timeline of one workgroup: (100 MHz wall clock << 8) | tag, appended per event
   unsigned long long *prof;
   int32_t prof_cap, prof_wg;
@@ -113,7 +93,7 @@ struct LsKParams {
 // Parameters of the GEMM prefill (host side launches; see ls_prefill.hip).
 struct LsPfParams {
   int32_t is_bf16, dm, qd, kvd, ffn, vocab, hd, nkv, max_seq, layers_used;
-  int32_t gs_x;                // columns per sum of squares of a residual row (LsKParams::gs_x)
+  int32_t ssq_nt;              // sums of squares per residual row (LsKParams::ssq_nt)
   float eps;
   const int32_t *tokens;
   const void *embed;

@@ -73,10 +73,12 @@ __global__ __launch_bounds__(256) void pf_rmsnorm_kernel(const float* x, const T
   for (int k = threadIdx.x; k < dm; k += 256) PT<T>::st(a + (size_t)m * dm + k, (xr[k] * r) * PT<T>::ld(gain + k));
 }
 
-// The last prompt row goes to row 0 of the decode residual buffer, with the sums of squares per
-// gs columns its RMSNorm needs; the head then runs in the decode kernel.
-__global__ __launch_bounds__(256) void pf_finish_kernel(const float* xrow, float* xbuf, float* ssq, int dm, int gs) {
-  for (int t = threadIdx.x; t * gs < dm; t += 256) {
+// The last prompt row goes to row 0 of the decode residual buffer, with its sum of squares spread
+// over the nt slots the decode kernel's RMSNorm adds up (slot t: columns [t*gs, (t+1)*gs), zero past
+// the end of the row); the head then runs in the decode kernel.
+__global__ __launch_bounds__(256) void pf_finish_kernel(const float* xrow, float* xbuf, float* ssq, int dm, int nt) {
+  const int gs = (dm + nt - 1) / nt;
+  for (int t = threadIdx.x; t < nt; t += 256) {
     float s = 0.f;
     for (int j = 0; j < gs && t * gs + j < dm; ++j) { const float v = xrow[t * gs + j]; xbuf[t * gs + j] = v; s += v * v; }
     ssq[t] = s;
@@ -693,6 +695,6 @@ extern "C" int ls_prefill_layers(const LsPfParams* p, const LsLayerW* host_layer
 }
 
 extern "C" int ls_prefill_finish(const LsPfParams* p, int last_row, hipStream_t s) {
-  pf_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(p->x_pf + (size_t)last_row * p->dm, p->xbuf, p->ssq, p->dm, p->gs_x);
+  pf_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(p->x_pf + (size_t)last_row * p->dm, p->xbuf, p->ssq, p->dm, p->ssq_nt);
   return hipGetLastError() == hipSuccess ? 0 : 1;
 }

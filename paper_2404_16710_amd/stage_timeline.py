@@ -62,7 +62,7 @@ def _layers(t, tag, kind):
 
 
 def _stage_table(times, pattern, weight_bytes, layer_end):
-    lines = ["| stage | total µs | barrier | input fetch | weights + products | epilogue | weight MB | stream GB/s |",
+    lines = ["| stage | total µs | barrier | input fetch | weights + products | epilogue | weight MB | GB/s over the stage |",
              "|---|---|---|---|---|---|---|---|"]
     idx = {g: i for i, g in enumerate(pattern)}            # first occurrence
     for k, (name, base) in enumerate(STAGES):
@@ -86,7 +86,7 @@ def _stage_table(times, pattern, weight_bytes, layer_end):
         stream = done[-1] - staged[0]          # later groups and chunks restage or reuse the rows in between
         epi = t_end - done[-1]
         lines.append(f"| {name} | {t_end - t0:.2f} | {barrier:.2f} | {fetch:.2f} | {stream:.2f} | {epi:.2f} | "
-                     f"{weight_bytes[k] / 1e6:.1f} | {weight_bytes[k] / stream / 1e3:.0f} |")
+                     f"{weight_bytes[k] / 1e6:.1f} | {weight_bytes[k] / (t_end - t0) / 1e3:.0f} |")
     return lines
 
 
@@ -109,11 +109,10 @@ def main():
     print(f"    python -m paper_2404_16710_amd.stage_timeline --config {a.config} --workgroup {a.workgroup}\n")
     print("Source: the kernel's own event recording (`ls_debug_timeline`), not a profiler; the kernel-level totals "
           "are in the rocprofv3 summaries beside this file.\n")
-    print("Times are averages over the layers one workgroup recorded (100 MHz wall clock); `stream GB/s` is the whole "
-          "stage's weight matrix over the time the workgroup spent between its input being staged and its last product "
-          "(all 256 workgroups stream their shares at the same time; the first register slots of a stage are requested "
-          "before its barrier, so this rate can exceed the HBM peak: what bounds a layer is the hand-over between "
-          "stages, i.e. the barrier, input fetch and epilogue columns, not the stream).\n")
+    print("Times are averages over the layers one workgroup recorded (100 MHz wall clock); `GB/s over the stage` is the "
+          "whole stage's weight matrix over the stage's total time, barrier and hand-over included (all 256 workgroups "
+          "stream their shares at the same time; the first register slots of a stage are requested before its barrier, "
+          "so the `weights + products` column alone understates the time those bytes had).\n")
     E, d = w.exit_layer, w.draft_len
 
     def drafted():

@@ -61,32 +61,49 @@ def test_generate_matches_oracle_and_full_greedy(name):
     gm.close()
 
 
-@pytest.mark.parametrize("name", ["c1", "c1-bf16", "gqa-hd128-bf16", "gqa2-f32"])
-def test_tagged_exchange_gives_the_same_bits_as_barriers(name):
-    """ls_set_exchange: polled, tagged hand-over between stages for passes of at most r rows, grid
-    barriers for the others.  Every setting must give identical tokens, round statistics, per-round
-    drafts / margins and hidden states; the barrier setting is the one checked against the oracle above."""
-    w = CASES[name]
+# Shapes whose many-row passes do not fit the LDS input region in one piece, so that the chunked
+# forms of the matmul input run: the down projection's input (rows x ffn) goes through two half
+# regions with the next chunk requested during the product of the current one; a normalised input
+# (rows x d_model) is re-staged chunk by chunk.  d_model 4352 also gives a workgroup two tiles in the
+# O / down projections (the form in which two tiles share the staged input).
+CHUNKED = {
+    "wide-ffn-bf16": W.Workload(_tiny("bf16", name="wide-ffn", n_layers=3, ffn_dim=4240), exit_layer=1, draft_len=15,
+                                n_prompt=21, n_new=36, resid_scale=0.1, gain_jitter=0.1),
+    "wide-ffn-f32": W.Workload(_tiny("f32", name="wide-ffn32", n_layers=3, ffn_dim=2128), exit_layer=2, draft_len=14,
+                               n_prompt=21, n_new=36, resid_scale=0.05, gain_jitter=0.1),
+    "wide-dm-bf16": W.Workload(_tiny("bf16", name="wide-dm", n_layers=2, d_model=4352, ffn_dim=528), exit_layer=1,
+                               draft_len=15, n_prompt=18, n_new=34, resid_scale=0.1),
+    "wide-dm-f32": W.Workload(_tiny("f32", name="wide-dm32", n_layers=2, d_model=2304, ffn_dim=528), exit_layer=1,
+                              draft_len=15, n_prompt=18, n_new=34, resid_scale=0.05),
+}
+
+
+@pytest.mark.parametrize("name", sorted(CHUNKED))
+def test_inputs_larger_than_the_lds_region_are_chunked_correctly(name):
+    """16-row (or 15-row) verification passes whose matmul inputs exceed the LDS region, against the
+    oracle: ids, round statistics where no near-tie interferes, hidden states of every position, and
+    bit-identical ids from one-row passes (full greedy), where nothing is chunked."""
+    w = CHUNKED[name]
     ws, prompt, om, gm = _setup(w)
+    ref = O.self_speculative(om, prompt, w.n_new, w.exit_layer, w.draft_len)
     cap = gm.debug_capture(True)
-    base = None
-    for rows in (0, 1, w.draft_len, 16):
-        gm.set_exchange(rows)
-        cap.zero_()
-        toks, st = gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
-        hid = cap.cpu().numpy().copy()
-        ar, _ = gm.generate(prompt, w.n_new, 0, 0)
-        gm.prefill(prompt)                      # one round through the step-by-step calls
-        gm.draft(w.exit_layer, w.draft_len)
-        gm.verify(w.exit_layer, w.draft_len)
-        rnd = gm.peek_round(w.draft_len)
-        got = (toks, ar, (st.rounds, st.drafted, st.accepted, st.generated), rnd)
-        if base is None:
-            base, base_hid = got, hid
-            assert toks == ar
-        else:
-            assert got == base, rows
-            assert np.array_equal(hid, base_hid), rows
+    toks, st = gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
+    hid = cap.cpu().numpy().copy()
+    gm.debug_capture(False)
+    ar, _ = gm.generate(prompt, w.n_new, 0, 0)
+    n = same_until_near_tie(toks, ref.tokens, ref.margins)
+    assert toks == ar and len(toks) == w.n_new
+    assert st.drafted == st.rounds * w.draft_len
+    full = O.greedy_full(om, prompt, w.n_new, want_hidden=True)
+    tol = 2e-2 if w.model.dtype == "bf16" else 1e-4
+    P = len(prompt)
+    rows = P + min(n, w.n_new - 1)          # positions whose input tokens agree with the oracle's
+    for l in range(w.model.n_layers):
+        assert rel_err_rows(hid[l, :rows], full.hidden[l + 1][:rows]) < tol, l
+    # the ablation runs all layers over 16 rows from the embedding table (the normalised input of the
+    # first layer then comes from embedding rows)
+    abl, st_abl = gm.generate_no_reuse(prompt, w.n_new, w.exit_layer, w.draft_len)
+    assert abl == toks and (st_abl.rounds, st_abl.accepted) == (st.rounds, st.accepted)
     gm.close()
 
 
@@ -161,7 +178,7 @@ def test_large_cache_capacity_groups_attention_tiles(name, max_seq):
     """With a large KV capacity one attention work item walks several 64-position tiles with a
     running softmax (16-bit models: in the MFMA accumulators of each wave; the grouped-query case
     has 24 query rows per KV head in its verify pass, i.e. two blocks of 16); the result must not
-    change, with barriers and with the tagged exchange."""
+    change."""
     w = CASES[name].with_(n_prompt=150, n_new=40)
     ws, prompt, om, gm = _setup(w, max_seq=max_seq)
     ref = O.greedy_full(om, prompt, w.n_new, want_hidden=True)
@@ -177,9 +194,6 @@ def test_large_cache_capacity_groups_attention_tiles(name, max_seq):
     for l in range(w.model.n_layers):
         assert rel_err_rows(hid[l], ref.hidden[l + 1]) < tol, l
     gm.debug_capture(False)
-    gm.set_exchange(16)
-    tagged, st_t = gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
-    assert tagged == toks and (st_t.rounds, st_t.accepted) == (st.rounds, st.accepted)
     gm.close()
 
 
@@ -325,15 +339,13 @@ def test_argument_errors_leave_no_work():
     gm.close()
 
 
-@pytest.mark.parametrize("rows", [0, 16])
-def test_expired_wait_is_reported_and_the_next_prompt_recovers(rows):
+def test_expired_wait_is_reported_and_the_next_prompt_recovers():
     """Failure handling, forced from the host: with a limit of one poll per wait some workgroup
     gives up at once, every workgroup then leaves (no kernel hangs or faults), the call reports
     LS_E_DEVICE, and after the limit is restored the same context generates the right tokens again."""
     from paper_2404_16710_amd.binding import LsError
     w = CASES["c1"]
     ws, prompt, om, gm = _setup(w)
-    gm.set_exchange(rows)
     want, _ = gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
     gm.debug_spin_limit(1)
     with pytest.raises(LsError) as ei:
