@@ -68,7 +68,7 @@ struct LsKParams {
   int32_t max_tiles;
   int32_t attn_ctiles;              // 64-position tiles per attention work item (from the cache capacity)
   float *cand;                      // [grid][16][4]
-  uint32_t *bar;                    // grid barrier counter
+  uint32_t *bar;                    // grid barrier counters (4096 bytes)
   LsState *state;
   float *capture;                   // [L][max_seq][dm] or null
   // ssq_nt: sums of squares per residual row (the number of workgroups); x_tiles: most weight tiles
