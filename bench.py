@@ -176,6 +176,28 @@ def stream_copy_gbs(model):
     return 4 * 2 * (1 << 30) / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
 
 
+def stream_read_gbs(model, workgroups):
+    """Read-only streaming reference: 2 GiB walked once per launch in the decode kernels' launch shape
+    (`workgroups` x 256 threads, 64 KB per workgroup in flight), ls_read_kernel."""
+    import torch
+    n = 2 << 30
+    src = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
+    sink = torch.empty(workgroups * 4096, dtype=torch.uint8, device="cuda:0")
+    def read():
+        rc = model.lib.ls_debug_read(ctypes.c_void_p(src.data_ptr()), n, ctypes.c_void_p(sink.data_ptr()), workgroups,
+                                     model._stream())
+        if rc != 0:
+            raise RuntimeError(f"ls_debug_read: {rc}")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    read()
+    ev[0].record()
+    for _ in range(4):
+        read()
+    ev[1].record()
+    torch.cuda.synchronize()
+    return 4 * n / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+
+
 def cpu_oracle_baseline(w, weights, prompt, E, d, n_sample, gpu_toks):
     """The oracle as it stands, on the host cores, for a bounded sample of the same job."""
     import numpy as np
@@ -284,6 +306,7 @@ def main() -> int:
                 "ms_decode": round(dy.ms_decode, 3), "acceptance": round(dy.acceptance, 4), "rounds": dy.rounds,
                 "drafts_leaving_at_exit_low": round(dy_low / max(dy.drafted, 1), 4), "same_ids": bool(dy_toks == toks)}
     stream_gbs = stream_copy_gbs(model)
+    read_gbs = {wg: stream_read_gbs(model, wg) for wg in (256, 2048)}
     traffic, traffic_rounds = committed_traffic(name, E, d, head["rounds"])
     out = {
         "metric": "generated tokens/s at batch 1, greedy self-speculative decoding (whole job: prefill + decode)",
@@ -309,6 +332,9 @@ def main() -> int:
                      "frac": head["roofline"]["frac"], "traffic": traffic, "traffic_profile_rounds": traffic_rounds,
                      "rounds": head["rounds"],
                      "stream_copy_gbs": round(stream_gbs, 1),
+                     "stream_read_gbs": {"decode_launch_shape_256_workgroups": round(read_gbs[256], 1),
+                                         "2048_workgroups": round(read_gbs[2048], 1)},
+                     "frac_of_stream_read": round(head["roofline"]["hbm_gbs"] / max(read_gbs.values()), 4),
                      "bytes_per_launch": head["roofline"]["bytes_per_launch"],
                      "ms_per_launch": head["roofline"]["ms_per_launch"]},
     }

@@ -191,6 +191,14 @@ int ls_debug_timeline(ls_ctx *ctx, unsigned long long *dev_events, int32_t capac
  * byte counters are scaled by.  Enqueue only. */
 int ls_debug_copy(void *dev_dst, const void *dev_src, size_t bytes, void *stream);
 
+/* Measurement aid: reads `bytes` of DEVICE memory once and writes nothing but 16 bytes per thread to
+ * `dev_sink` (DEVICE, at least workgroups * 4096 bytes; both pointers 16-byte aligned), in the launch
+ * shape of the decode kernels: `workgroups` workgroups of 256 threads (1..4096; the decode kernels run
+ * 256), each walking a contiguous share with 16-byte loads, 64 KB per workgroup in flight.  `bytes` must
+ * be a multiple of workgroups * 65536.  Its rate is the practical ceiling of a stage's weight stream
+ * (ls_read_kernel in a profiler's kernel trace).  Enqueue only; LS_E_ARG on a bad argument. */
+int ls_debug_read(const void *dev_src, size_t bytes, void *dev_sink, int32_t workgroups, void *stream);
+
 /* Debug aid: how many polls a workgroup spends in one wait for the others before it gives up
  * (0 restores the default of about four million).  When a wait expires every workgroup leaves, the
  * call that launched the kernel returns LS_E_DEVICE, and the next ls_prefill / ls_generate* / ls_score

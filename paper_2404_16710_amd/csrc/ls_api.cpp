@@ -17,6 +17,7 @@
 extern "C" int ls_launch_program(const LsKParams* p, int dtype_is_bf16, int grid, hipStream_t stream);
 extern "C" int ls_kernel_setup(int dtype_is_bf16, int hd, int* max_blocks_per_cu);
 extern "C" int ls_launch_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
+extern "C" int ls_launch_read(const void* src, size_t bytes, void* sink, int workgroups, hipStream_t stream);
 extern "C" int ls_prefill_layers(const LsPfParams* p, const LsLayerW* host_layers, int pos0, int M, hipStream_t s);
 extern "C" int ls_prefill_finish(const LsPfParams* p, int last_row, hipStream_t s);
 extern "C" int ls_static_scratch_ptr(void** ptr);
@@ -517,6 +518,12 @@ int ls_debug_timeline(ls_ctx* c, unsigned long long* dev_events, int32_t capacit
 int ls_debug_copy(void* dev_dst, const void* dev_src, size_t bytes, void* stream) {
   if (!dev_dst || !dev_src || bytes == 0 || bytes % 16 || ((uintptr_t)dev_dst | (uintptr_t)dev_src) % 16) return LS_E_ARG;
   return ls_launch_copy(dev_src, dev_dst, bytes, static_cast<hipStream_t>(stream)) == 0 ? LS_OK : LS_E_HIP;
+}
+
+int ls_debug_read(const void* dev_src, size_t bytes, void* dev_sink, int32_t workgroups, void* stream) {
+  if (!dev_src || !dev_sink || workgroups < 1 || workgroups > 4096 || ((uintptr_t)dev_src | (uintptr_t)dev_sink) % 16) return LS_E_ARG;
+  if (bytes == 0 || bytes % ((size_t)workgroups * 256 * 16 * 16)) return LS_E_ARG;
+  return ls_launch_read(dev_src, bytes, dev_sink, workgroups, static_cast<hipStream_t>(stream)) == 0 ? LS_OK : LS_E_HIP;
 }
 
 const char* ls_strerror(int code) {

@@ -24,6 +24,37 @@ extern "C" int ls_launch_copy(const void* src, void* dst, size_t bytes, hipStrea
   return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
+// Read-only stream in the launch shape of the decode kernels: every workgroup walks its own contiguous
+// share with 16-byte loads, 16 per lane in flight (the 64 KB per compute unit that the decode kernels
+// keep in flight for weights), and folds what it read into one 16-byte value per thread so that the
+// loads stay.  The rate of this kernel is what a stage's weight stream can reach at best.
+__global__ __launch_bounds__(256) void ls_read_kernel(const uint4* __restrict__ src, size_t n16, uint4* __restrict__ sink) {
+  constexpr int D = 16;
+  const size_t share = n16 / gridDim.x;                 // a multiple of 256 * D (checked by the caller)
+  const uint4* p = src + (size_t)blockIdx.x * share + threadIdx.x;
+  uint4 v[D];
+#pragma unroll
+  for (int q = 0; q < D; ++q) v[q] = p[(size_t)q * 256];
+  uint4 acc = make_uint4(0, 0, 0, 0);
+  const size_t steps = share / (256 * D);
+  for (size_t i = 1; i < steps; ++i) {
+    const uint4* pn = p + i * (size_t)(256 * D);
+#pragma unroll
+    for (int q = 0; q < D; ++q) {
+      acc.x ^= v[q].x; acc.y ^= v[q].y; acc.z ^= v[q].z; acc.w ^= v[q].w;
+      v[q] = pn[(size_t)q * 256];
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < D; ++q) { acc.x ^= v[q].x; acc.y ^= v[q].y; acc.z ^= v[q].z; acc.w ^= v[q].w; }
+  sink[(size_t)blockIdx.x * 256 + threadIdx.x] = acc;
+}
+
+extern "C" int ls_launch_read(const void* src, size_t bytes, void* sink, int workgroups, hipStream_t stream) {
+  ls_read_kernel<<<dim3(workgroups), dim3(256), 0, stream>>>(static_cast<const uint4*>(src), bytes / 16, static_cast<uint4*>(sink));
+  return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
 // Workspace of ls_generate_static: callers that may not allocate device memory get the KV cache and all
 // per-stage scratch from this fixed array instead of a buffer of their own.  Every GPU the library runs
 // on holds its own copy at its own address; host code never uses the array's name as an address, only

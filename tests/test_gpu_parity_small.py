@@ -339,6 +339,27 @@ def test_argument_errors_leave_no_work():
     gm.close()
 
 
+def test_read_only_stream_reference_reads_every_byte_once():
+    """The measurement aid ls_debug_read folds all it reads into 16 bytes per thread with xor: the
+    xor over its sink equals the xor over the source's 16-byte units, for both launch shapes."""
+    import ctypes
+    import torch
+    from paper_2404_16710_amd import binding as B
+    lib = B.lib()
+    g = torch.Generator().manual_seed(5)
+    src_h = torch.randint(-2**31, 2**31 - 1, (1 << 23,), dtype=torch.int32, generator=g)   # 32 MiB
+    want = src_h.view(-1, 4).numpy()
+    want = np.bitwise_xor.reduce(want, axis=0)
+    src = src_h.to("cuda:0")
+    for wg in (256, 512):
+        sink = torch.zeros(wg * 1024, dtype=torch.int32, device="cuda:0")
+        stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        assert lib.ls_debug_read(ctypes.c_void_p(src.data_ptr()), src.numel() * 4, ctypes.c_void_p(sink.data_ptr()), wg, stream) == 0
+        torch.cuda.synchronize()
+        got = np.bitwise_xor.reduce(sink.cpu().view(-1, 4).numpy(), axis=0)
+        assert (got == want).all(), wg
+
+
 def test_expired_wait_is_reported_and_the_next_prompt_recovers():
     """Failure handling, forced from the host: with a limit of one poll per wait some workgroup
     gives up at once, every workgroup then leaves (no kernel hangs or faults), the call reports

@@ -69,6 +69,11 @@ def test_null_and_misaligned_arguments_are_rejected_without_a_gpu():
                      ("ls_debug_capture", (None, None)), ("ls_set_launch", (None, 1)),
                      ("ls_set_prompt_tiles", (None, 64)), ("ls_debug_spin_limit", (None, 1))):
         assert getattr(lib, fn)(*args) == -1, fn
+    # the read-only stream reference: null or misaligned pointers, no workgroups, a size that does not split evenly
+    for args in ((None, 1 << 24, C.c_void_p(256), 256, None), (C.c_void_p(256), 1 << 24, None, 256, None),
+                 (C.c_void_p(264), 1 << 24, C.c_void_p(256), 256, None), (C.c_void_p(256), 1 << 24, C.c_void_p(256), 0, None),
+                 (C.c_void_p(256), (1 << 24) + 16, C.c_void_p(256), 256, None), (C.c_void_p(256), 0, C.c_void_p(256), 256, None)):
+        assert lib.ls_debug_read(*args) == -1, args
     assert b"capacity" in lib.ls_strerror(-3) and b"ok" == lib.ls_strerror(0)
     lib.ls_destroy(None)                                     # harmless
 
