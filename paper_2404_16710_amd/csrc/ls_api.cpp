@@ -45,6 +45,8 @@ bool config_ok(const ls_config* c) {
   if (c->n_q_heads / c->n_kv_heads > 4) return false;
   if (c->d_model < 16 || c->d_model % 16 || c->ffn_dim < 16 || c->ffn_dim % 16) return false;
   if (c->vocab < 16 || c->vocab % 16) return false;
+  // (the kernels split a stage's rows over the workgroups with 32-bit products of row units and workgroup ids)
+  if (c->d_model > (1 << 20) || c->ffn_dim > (1 << 22) || c->vocab > (1 << 22) || c->n_q_heads > 4096) return false;
   if (c->max_draft < 1 || c->max_draft > LS_MAX_ROWS - 1) return false;
   if (c->max_seq < 2 || c->max_seq > 32768) return false;
   if (!(c->rms_eps > 0.f) || !(c->rope_base > 1.f)) return false;
