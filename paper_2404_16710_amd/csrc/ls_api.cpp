@@ -127,6 +127,13 @@ void set_decomposition(ls_ctx* c) {
   int C = 1;
   while (g.n_kv_heads * ((max_tiles + C - 1) / C) > c->grid && C < max_tiles) ++C;
   c->base.attn_ctiles = C;
+  // Settled K/V tiles: through the caches when the whole KV cache can stay in the 256 MB memory-side cache
+  // between two passes (short contexts, small models: the tiles then come back from a cache, measured 1 us
+  // per layer faster on the 1.5B and 8B shapes); with coherent loads otherwise (a large cache is streamed
+  // once per pass, and coherent requests were 1 us per layer faster on the 13B shape).  Same bytes, same
+  // arithmetic either way.
+  const size_t kv_bytes = 2 * (size_t)g.n_layers * g.max_seq * g.n_kv_heads * g.head_dim * (g.dtype == LS_BF16 ? 2 : 4);
+  c->base.kv_through_caches = kv_bytes <= ((size_t)192 << 20);
 }
 
 int launch(ls_ctx* c, LsKParams& p, hipStream_t s) {

@@ -67,6 +67,8 @@ struct LsKParams {
   uint32_t *attn_cnt;               // [nkv]
   int32_t max_tiles;
   int32_t attn_ctiles;              // 64-position tiles per attention work item (from the cache capacity)
+  int32_t kv_through_caches;        // settled K/V tiles are read with cacheable loads: set when the whole KV cache
+                                    // is small enough to stay in the memory-side cache between passes
   float *cand;                      // [grid][16][4]
   uint32_t *bar;                    // grid barrier counters (4096 bytes)
   LsState *state;
