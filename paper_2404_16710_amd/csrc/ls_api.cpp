@@ -159,8 +159,8 @@ int read_state(ls_ctx* c, LsState* st, hipStream_t s) {
   return LS_OK;
 }
 
-// After a device-side error the tags, counters and the error flag are unreliable: start them over
-// (counters, state and tagged buffers are contiguous in the workspace).
+// After a device-side error the counters and the error flag are unreliable: start them over (row
+// buffers, counters and state are contiguous in the workspace).
 int recover(ls_ctx* c, hipStream_t s) {
   if (!c->poisoned) return LS_OK;
   if (hipMemsetAsync(c->ws + c->lay.xbuf, 0, c->lay.x_pf - c->lay.xbuf, s) != hipSuccess) return LS_E_HIP;
