@@ -205,6 +205,13 @@ int ls_debug_read(const void *dev_src, size_t bytes, void *dev_sink, int32_t wor
  * starts from rebuilt counters.  A limit of 1 makes that path testable without a hung kernel. */
 int ls_debug_spin_limit(ls_ctx *ctx, int32_t polls);
 
+/* Debug aid: how later calls read K/V tiles that no pass of the current round writes.  0 (default): with
+ * cacheable loads when the whole KV cache of the configuration is at most 192 MB (it then survives in the
+ * memory-side cache from pass to pass), with coherent loads otherwise; 1: always cacheable; 2: always
+ * coherent.  The bytes read and the arithmetic are the same either way; the setting selects one of two
+ * instantiations of the attention stage, and tests use it to run both on one model.  LS_E_RANGE otherwise. */
+int ls_debug_kv_policy(ls_ctx *ctx, int32_t policy);
+
 /* Launch shape: workgroups per compute unit (1 or 2) used by later calls; 0 restores the default.
  * Returns the number of workgroups a launch will use, or a negative error. */
 int ls_set_launch(ls_ctx *ctx, int32_t workgroups_per_cu);

@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 EXPORTS = (
     "ls_workspace_bytes", "ls_load_weights", "ls_prefill", "ls_draft", "ls_verify", "ls_generate",
     "ls_generate_no_reuse", "ls_generate_dynamic", "ls_generate_early_exit", "ls_score", "ls_probe_layers", "ls_get_state", "ls_peek_round", "ls_debug_capture",
-    "ls_debug_timeline", "ls_debug_copy", "ls_debug_read", "ls_set_launch", "ls_set_prompt_tiles", "ls_debug_spin_limit", "ls_strerror", "ls_destroy",
+    "ls_debug_timeline", "ls_debug_copy", "ls_debug_read", "ls_set_launch", "ls_set_prompt_tiles", "ls_debug_spin_limit", "ls_debug_kv_policy", "ls_strerror", "ls_destroy",
     "ls_generate_static", "ls_static_workspace_limit",
 )
 
@@ -122,6 +122,8 @@ def lib() -> C.CDLL:
     L.ls_debug_read.argtypes = [vp, C.c_size_t, vp, i32, vp]
     L.ls_debug_spin_limit.restype = C.c_int
     L.ls_debug_spin_limit.argtypes = [vp, i32]
+    L.ls_debug_kv_policy.restype = C.c_int
+    L.ls_debug_kv_policy.argtypes = [vp, i32]
     L.ls_generate_static.restype = C.c_int
     L.ls_generate_static.argtypes = [C.POINTER(ls_config), C.POINTER(ls_weights), vp, i32, i32, i32, i32, i32, vp,
                                      C.POINTER(ls_stats), vp]
@@ -275,6 +277,9 @@ class LsModel:
 
     def debug_spin_limit(self, polls: int) -> None:
         _check(self.lib.ls_debug_spin_limit(self.ctx, polls), "ls_debug_spin_limit")
+
+    def debug_kv_policy(self, policy: int) -> None:
+        _check(self.lib.ls_debug_kv_policy(self.ctx, policy), "ls_debug_kv_policy")
 
     def set_prompt_tiles(self, rows: int) -> None:
         _check(self.lib.ls_set_prompt_tiles(self.ctx, rows), "ls_set_prompt_tiles")

@@ -105,6 +105,7 @@ struct ls_ctx {
   std::vector<LsLayerW> host_layers;
   LsPfParams pf;
   bool gemm_prefill;
+  int kv_policy;   // 0: settled K/V tiles through the caches when the KV cache is small; 1: always; 2: never
 };
 
 namespace {
@@ -133,7 +134,7 @@ void set_decomposition(ls_ctx* c) {
   // once per pass, and coherent requests were 1 us per layer faster on the 13B shape).  Same bytes, same
   // arithmetic either way.
   const size_t kv_bytes = 2 * (size_t)g.n_layers * g.max_seq * g.n_kv_heads * g.head_dim * (g.dtype == LS_BF16 ? 2 : 4);
-  c->base.kv_through_caches = kv_bytes <= ((size_t)192 << 20);
+  c->base.kv_through_caches = c->kv_policy == 0 ? kv_bytes <= ((size_t)192 << 20) : c->kv_policy == 1;
 }
 
 int launch(ls_ctx* c, LsKParams& p, hipStream_t s) {
@@ -203,6 +204,7 @@ static int init_ctx(ls_ctx* c, const ls_config* cfg, const ls_weights* w, void* 
   c->capture = nullptr;
   c->prof = nullptr; c->prof_cap = 0; c->prof_wg = 0;
   c->prefilled = c->drafted = false;
+c->kv_policy = 0;
   c->poisoned = false;
   c->pos_bound = 0;
 
@@ -303,6 +305,14 @@ int ls_debug_spin_limit(ls_ctx* c, int32_t polls) {
   if (!c) return LS_E_ARG;
   if (polls < 0) return LS_E_RANGE;
   c->base.spin_limit = polls == 0 ? (1 << 22) : polls;
+  return LS_OK;
+}
+
+int ls_debug_kv_policy(ls_ctx* c, int32_t policy) {
+  if (!c) return LS_E_ARG;
+  if (policy < 0 || policy > 2) return LS_E_RANGE;
+  c->kv_policy = policy;
+  set_decomposition(c);
   return LS_OK;
 }
 

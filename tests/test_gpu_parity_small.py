@@ -197,6 +197,28 @@ def test_large_cache_capacity_groups_attention_tiles(name, max_seq):
     gm.close()
 
 
+@pytest.mark.parametrize("name", ["c1", "c1-bf16", "gqa-hd128-bf16"])
+@pytest.mark.parametrize("max_seq", [256, 4096 + 512])
+def test_both_cache_policies_of_the_attention_stage_give_the_same_tokens(name, max_seq):
+    """The attention stage exists once per way of reading settled K/V tiles (through the caches, or with
+    coherent loads) and per item shape (one tile, or several): the library picks by cache size, the test
+    forces each policy on a short and on a long cache.  Same bytes, same arithmetic: identical ids, and
+    the self-speculative ids equal the full-greedy ids under either."""
+    w = CASES[name].with_(n_prompt=150, n_new=40)
+    ws, prompt, om, gm = _setup(w, max_seq=max_seq)
+    ref = O.greedy_full(om, prompt, w.n_new)
+    outs = []
+    for policy in (1, 2, 0):
+        gm.debug_kv_policy(policy)
+        toks, _ = gm.generate(prompt, w.n_new, w.exit_layer, w.draft_len)
+        ar, _ = gm.generate(prompt, w.n_new, 0, 0)
+        assert toks == ar, policy
+        outs.append(toks)
+    assert outs[0] == outs[1] == outs[2]
+    same_until_near_tie(outs[0], ref.tokens, ref.margins)
+    gm.close()
+
+
 @pytest.mark.parametrize("name,n_prompt", [("c1", 150), ("c1-bf16", 131), ("gqa-hd128-bf16", 257), ("gqa2-f32", 64),
                                            ("c1", 2100), ("gqa-hd128-bf16", 2085)])   # the last two: more than one chunk of 2048 prompt rows
 def test_prefill_hidden_states_and_cache(name, n_prompt):

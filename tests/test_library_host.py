@@ -67,7 +67,8 @@ def test_null_and_misaligned_arguments_are_rejected_without_a_gpu():
     for fn, args in (("ls_prefill", (None, None, 4, None)), ("ls_draft", (None, 1, 1, None)),
                      ("ls_verify", (None, 1, 1, None)), ("ls_get_state", (None, None, None, None, None)),
                      ("ls_debug_capture", (None, None)), ("ls_set_launch", (None, 1)),
-                     ("ls_set_prompt_tiles", (None, 64)), ("ls_debug_spin_limit", (None, 1))):
+                     ("ls_set_prompt_tiles", (None, 64)), ("ls_debug_spin_limit", (None, 1)),
+                     ("ls_debug_kv_policy", (None, 1))):
         assert getattr(lib, fn)(*args) == -1, fn
     # the read-only stream reference: null or misaligned pointers, no workgroups, a size that does not split evenly
     for args in ((None, 1 << 24, C.c_void_p(256), 256, None), (C.c_void_p(256), 1 << 24, None, 256, None),
