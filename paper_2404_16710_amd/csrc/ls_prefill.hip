@@ -86,15 +86,24 @@ __global__ __launch_bounds__(256) void pf_finish_kernel(const float* xrow, float
 }
 
 // ------------------------------------------------------------------------------------------
-enum { EPI_ROPE_Q = 0, EPI_ROPE_K = 1, EPI_V = 2, EPI_RESID = 3, EPI_GU = 4 };
+// EPI_QKV: the three projections of the attention input in one launch; a tile's columns decide which
+// matrix it multiplies and which of the first three epilogues it takes (q_dim and kv_dim are multiples
+// of the tile width there, so a tile never straddles two matrices).  Three launches of 640 tiles each
+// (13B shape, 1024 prompt rows) fill the 512 resident workgroups one and a quarter times each; one
+// launch of 1920 tiles fills them three and three quarter times.
+enum { EPI_ROPE_Q = 0, EPI_ROPE_K = 1, EPI_V = 2, EPI_RESID = 3, EPI_GU = 4, EPI_QKV = 5 };
 
 struct PfGemm {
   const void* A;    // [M][K] activations (model dtype), row stride lda
   int lda;
   const void* W;    // [N][K] weights
-  const void* W2;   // second weight matrix (gate/up: W = gate, W2 = up)
-  int M, N, K;
+  const void* W2;   // second weight matrix (gate/up: W = gate, W2 = up; QKV: W = wq, W2 = wk, W3 = wv)
+  const void* W3;
+  int M, N, K;      // (QKV: N = q_dim + 2 kv_dim, N_q = q_dim, N_kv = kv_dim)
+  int N_q, N_kv;
   void* out;        // q rows [M][ldo] / SwiGLU rows [M][ldo] (model dtype); KV cache base for K, V
+  void* out_k;      // QKV: the K and the V cache (out = q rows)
+  void* out_v;
   int ldo;
   float* x;         // residual rows [M][N] fp32 (EPI_RESID)
   float* capture;   // optional copy of the new residual rows, [max_seq][N] of this layer
@@ -142,9 +151,17 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
   const int r = lane & 15, gq = lane >> 4;
   int tile_m, tile_n;
   pf_tile_of((g.M + BMT - 1) / BMT, (g.N + BN - 1) / BN, tile_m, tile_n);
-  const int n0 = tile_n * BN, m0 = tile_m * BMT;
+  int n0 = tile_n * BN;
+  const int m0 = tile_m * BMT;
   const T* Ag = static_cast<const T*>(g.A);
   const T* Wg[2] = {static_cast<const T*>(g.W), static_cast<const T*>(g.W2)};
+  int epi = EPI, n_cols = g.N;   // this tile's epilogue and the columns of its matrix (uniform; constants unless QKV)
+  void* outp = g.out;
+  if (EPI == EPI_QKV) {
+    if (n0 < g.N_q) { epi = EPI_ROPE_Q; n_cols = g.N_q; }
+    else if (n0 < g.N_q + g.N_kv) { epi = EPI_ROPE_K; n0 -= g.N_q; n_cols = g.N_kv; Wg[0] = static_cast<const T*>(g.W2); outp = g.out_k; }
+    else { epi = EPI_V; n0 -= g.N_q + g.N_kv; n_cols = g.N_kv; Wg[0] = static_cast<const T*>(g.W3); outp = g.out_v; }
+  }
 
   f32x4 acc[NW][RT][8];
 #pragma unroll
@@ -168,7 +185,7 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
     for (int i = 0; i < 4; ++i) {
       const int unit = tid + 256 * i, row = unit >> 3, u = unit & 7;
       const int k = k0 + u * EPV, na = n0 + row;
-      const bool wok = k < g.K && na < g.N;
+      const bool wok = k < g.K && na < n_cols;
 #pragma unroll
       for (int w = 0; w < NW; ++w) {
         const uint4 vw = *reinterpret_cast<const uint4*>(Wg[w] + (size_t)(wok ? na : 0) * g.K + (wok ? k : 0));
@@ -226,19 +243,19 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int n = n0 + 16 * j + r;
-        if (n >= g.N) continue;
+        if (n >= n_cols) continue;
         const float v = acc[0][i][j][jj];
-        if (EPI == EPI_RESID) {
+        if (epi == EPI_RESID) {
           float* xr = g.x + (size_t)m * g.N + n;
           const float nv = *xr + v;
           *xr = nv;
           if (g.capture != nullptr) g.capture[(size_t)pos * g.N + n] = nv;
-        } else if (EPI == EPI_GU) {
+        } else if (epi == EPI_GU) {
           const float up = acc[NW - 1][i][j][jj];
-          PT<T>::st(static_cast<T*>(g.out) + (size_t)m * g.ldo + n, (v / (1.0f + expf(-v))) * up);
-        } else if (EPI == EPI_V) {
+          PT<T>::st(static_cast<T*>(outp) + (size_t)m * g.ldo + n, (v / (1.0f + expf(-v))) * up);
+        } else if (epi == EPI_V) {
           const int h = n / g.hd, d = n - h * g.hd;
-          PT<T>::st(static_cast<T*>(g.out) + (((size_t)g.layer * g.nkv + h) * g.max_seq + pos) * g.hd + d, v);
+          PT<T>::st(static_cast<T*>(outp) + (((size_t)g.layer * g.nkv + h) * g.max_seq + pos) * g.hd + d, v);
         } else {
           // rotation mixes columns d and d + hd/2 of one head; both sit in this lane (tile j and j + half/16)
           const int h = n / g.hd, d = n - h * g.hd;
@@ -247,12 +264,12 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
             const float b = (g.hd == 128) ? acc[0][i][(j + 4) & 7][jj] : acc[0][i][(j + 2) & 7][jj];
             const float c = g.rope_cos[(size_t)pos * half + d], s = g.rope_sin[(size_t)pos * half + d];
             const float lo = v * c - b * s, hi = b * c + v * s;
-            if (EPI == EPI_ROPE_Q) {
-              T* dst = static_cast<T*>(g.out) + (size_t)m * g.ldo + h * g.hd;
+            if (epi == EPI_ROPE_Q) {
+              T* dst = static_cast<T*>(outp) + (size_t)m * g.ldo + h * g.hd;
               PT<T>::st(dst + d, lo);
               PT<T>::st(dst + d + half, hi);
             } else {
-              T* dst = static_cast<T*>(g.out) + (((size_t)g.layer * g.nkv + h) * g.max_seq + pos) * g.hd;
+              T* dst = static_cast<T*>(outp) + (((size_t)g.layer * g.nkv + h) * g.max_seq + pos) * g.hd;
               PT<T>::st(dst + d, lo);
               PT<T>::st(dst + d + half, hi);
             }
@@ -436,6 +453,7 @@ static bool use_small_tiles(const PfGemm& g) {
 
 template <typename T, int EPI>
 hipError_t launch_gemm(const PfGemm& g, hipStream_t s) {
+  if constexpr (EPI != EPI_QKV) {   // (the fused launch exists for the large tiles only; its caller checks)
   if (use_small_tiles(g)) {
     constexpr int NW = (EPI == EPI_GU) ? 2 : 1;
     constexpr int smem = ks_smem_bytes<NW>();
@@ -449,6 +467,7 @@ hipError_t launch_gemm(const PfGemm& g, hipStream_t s) {
     dim3 grid(((g.N + BN - 1) / BN) * ((g.M + SBM - 1) / SBM));
     pf_gemm_ks_kernel<T, EPI><<<grid, dim3(256), smem, s>>>(g);
     return hipGetLastError();
+  }
   }
   // 64-row tiles while 128-row tiles would leave fewer than about two per compute unit
   const long tiles128 = (long)((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM);
@@ -669,11 +688,23 @@ int run_layers(const LsPfParams& p, const LsLayerW* lw, int pos0, int M, hipStre
     g.A = p.a_pf; g.lda = dm; g.M = M; g.K = dm; g.hd = p.hd; g.pos0 = pos0; g.max_seq = p.max_seq; g.nkv = p.nkv;
     g.layer = l; g.rope_cos = p.rope_cos; g.rope_sin = p.rope_sin; g.tile_rows = p.tile_rows;
     g.W = W.wq; g.N = qd; g.out = p.q_pf; g.ldo = qd;
-    if (launch_gemm<T, EPI_ROPE_Q>(g, s) != hipSuccess) return 1;
-    g.W = W.wk; g.N = kvd; g.out = p.kcache;
-    if (launch_gemm<T, EPI_ROPE_K>(g, s) != hipSuccess) return 1;
-    g.W = W.wv; g.N = kvd; g.out = p.vcache;
-    if (launch_gemm<T, EPI_V>(g, s) != hipSuccess) return 1;
+    bool fused = false;
+    if (qd % BN == 0 && kvd % BN == 0) {
+      // one launch for the three projections, when it would run on the large tiles anyway
+      PfGemm f = g;
+      f.W2 = W.wk; f.W3 = W.wv; f.N = qd + 2 * kvd; f.N_q = qd; f.N_kv = kvd; f.out_k = p.kcache; f.out_v = p.vcache;
+      if (!use_small_tiles(f) && !use_small_tiles(g)) {
+        if (launch_gemm<T, EPI_QKV>(f, s) != hipSuccess) return 1;
+        fused = true;
+      }
+    }
+    if (!fused) {
+      if (launch_gemm<T, EPI_ROPE_Q>(g, s) != hipSuccess) return 1;
+      g.W = W.wk; g.N = kvd; g.out = p.kcache;
+      if (launch_gemm<T, EPI_ROPE_K>(g, s) != hipSuccess) return 1;
+      g.W = W.wv; g.N = kvd; g.out = p.vcache;
+      if (launch_gemm<T, EPI_V>(g, s) != hipSuccess) return 1;
+    }
     if (launch_attn<T>(p, l, pos0, M, s) != hipSuccess) return 1;
     g.A = p.o_pf; g.lda = qd; g.K = qd; g.W = W.wo; g.N = dm; g.x = p.x_pf; g.capture = nullptr;
     if (launch_gemm<T, EPI_RESID>(g, s) != hipSuccess) return 1;
