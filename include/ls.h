@@ -218,7 +218,9 @@ int ls_set_launch(ls_ctx *ctx, int32_t workgroups_per_cu);
 
 /* Shape of the prompt pass used by later calls.  Prompts of 32 or more ids run as GEMMs over all
  * rows of a chunk, with output tiles of 128, 64 or 32 rows chosen from the number of tiles the
- * launch would have (rows = 0, the default); 32, 64 or 128 force that tile height, 16 sends every
+ * launch would have (rows = 0, the default); 32, 64 or 128 force that tile height, 160 forces 64-row
+ * tiles that are 160 instead of 128 columns wide in the products into the residual rows (where 160
+ * divides d_model; the default picks them when they fill the chip in fewer rounds), 16 sends every
  * prompt through the 16-row passes of the decode kernel.  All choices compute the same operation
  * and differ in the order of the floating-point sums only.  Host state only: no GPU work.
  * Returns LS_OK, LS_E_ARG for a null context or LS_E_RANGE for any other value. */

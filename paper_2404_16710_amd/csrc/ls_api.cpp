@@ -295,7 +295,7 @@ int ls_load_weights(const ls_config* cfg, const ls_weights* w, void* dev_workspa
 
 int ls_set_prompt_tiles(ls_ctx* c, int32_t rows) {
   if (!c) return LS_E_ARG;
-  if (rows != 0 && rows != 16 && rows != 32 && rows != 64 && rows != 128) return LS_E_RANGE;
+  if (rows != 0 && rows != 16 && rows != 32 && rows != 64 && rows != 128 && rows != 160) return LS_E_RANGE;
   c->gemm_prefill = rows != 16;
   c->pf.tile_rows = rows == 16 ? 0 : rows;
   return LS_OK;

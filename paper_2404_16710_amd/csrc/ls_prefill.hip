@@ -137,21 +137,26 @@ constexpr int ROWB = 128;          // bytes of K per tile row
 constexpr int ROWP = ROWB + 16;    // padded LDS row
 
 // BMT: rows of the output tile (128, or 64 when there are too few 128-row tiles to keep several
-// workgroups resident per compute unit); a wave computes BMT/4 rows x 128 columns.
-template <typename T, int EPI, int BMT>
+// workgroups resident per compute unit); a wave computes BMT/4 rows x BNT columns.
+// BNT: columns of the output tile, 128, or 160 for the products into the residual rows when that makes
+// the number of tiles fit the resident workgroups better (see launch_gemm).
+template <typename T, int EPI, int BMT, int BNT = BN>
 __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
+  static_assert(BNT % 32 == 0 && (BNT == BN || EPI == EPI_RESID), "rotations pair columns inside a 128-column tile");
+  constexpr int NF = BNT / 16;          // 16-column fragments per tile
+  constexpr int LW = BNT * 8 / 256;     // 16-byte units of a W tile per thread
   constexpr int EPV = PT<T>::EPV;
   constexpr int BK = ROWB / (int)sizeof(T);
   constexpr int NW = (EPI == EPI_GU) ? 2 : 1;
   constexpr int RT = BMT / 64;          // 16-row tiles per wave
   constexpr int LA = BMT * 8 / 256;     // 16-byte units of the A tile per thread
   __shared__ __align__(16) char As[BMT * ROWP];
-  __shared__ __align__(16) char Ws[NW][BN * ROWP];
+  __shared__ __align__(16) char Ws[NW][BNT * ROWP];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, gq = lane >> 4;
   int tile_m, tile_n;
-  pf_tile_of((g.M + BMT - 1) / BMT, (g.N + BN - 1) / BN, tile_m, tile_n);
-  int n0 = tile_n * BN;
+  pf_tile_of((g.M + BMT - 1) / BMT, (g.N + BNT - 1) / BNT, tile_m, tile_n);
+  int n0 = tile_n * BNT;
   const int m0 = tile_m * BMT;
   const T* Ag = static_cast<const T*>(g.A);
   const T* Wg[2] = {static_cast<const T*>(g.W), static_cast<const T*>(g.W2)};
@@ -163,15 +168,15 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
     else { epi = EPI_V; n0 -= g.N_q + g.N_kv; n_cols = g.N_kv; Wg[0] = static_cast<const T*>(g.W3); outp = g.out_v; }
   }
 
-  f32x4 acc[NW][RT][8];
+  f32x4 acc[NW][RT][NF];
 #pragma unroll
   for (int w = 0; w < NW; ++w)
 #pragma unroll
     for (int i = 0; i < RT; ++i)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) acc[w][i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int j = 0; j < NF; ++j) acc[w][i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  uint4 ra[LA], rw[NW][4];
+  uint4 ra[LA], rw[NW][LW];
   auto gload = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
@@ -182,7 +187,7 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
       ra[i] = aok ? va : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < LW; ++i) {
       const int unit = tid + 256 * i, row = unit >> 3, u = unit & 7;
       const int k = k0 + u * EPV, na = n0 + row;
       const bool wok = k < g.K && na < n_cols;
@@ -200,7 +205,7 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
       *reinterpret_cast<uint4*>(As + row * ROWP + u * 16) = ra[i];
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < LW; ++i) {
       const int unit = tid + 256 * i, row = unit >> 3, u = unit & 7;
 #pragma unroll
       for (int w = 0; w < NW; ++w) *reinterpret_cast<uint4*>(Ws[w] + row * ROWP + u * 16) = rw[w][i];
@@ -222,7 +227,7 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
 #pragma unroll
       for (int w = 0; w < NW; ++w) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < NF; ++j) {
           const uint4 fb = *reinterpret_cast<const uint4*>(Ws[w] + (j * 16 + r) * ROWP + (s * 4 + gq) * 16);
 #pragma unroll
           for (int i = 0; i < RT; ++i) PT<T>::mma(acc[w][i][j], fa[i], fb);
@@ -241,7 +246,7 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
       if (m >= g.M) continue;
       const int pos = g.pos0 + m;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
+      for (int j = 0; j < NF; ++j) {
         const int n = n0 + 16 * j + r;
         if (n >= n_cols) continue;
         const float v = acc[0][i][j][jj];
@@ -261,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void pf_gemm_kernel(const PfGemm g) {
           const int h = n / g.hd, d = n - h * g.hd;
           if (d < half) {
             // partner tile: 4 tiles on for head_dim 128, 2 tiles on for head_dim 64 (static indices)
-            const float b = (g.hd == 128) ? acc[0][i][(j + 4) & 7][jj] : acc[0][i][(j + 2) & 7][jj];
+            const float b = (g.hd == 128) ? acc[0][i][(j + 4) % NF][jj] : acc[0][i][(j + 2) % NF][jj];
             const float c = g.rope_cos[(size_t)pos * half + d], s = g.rope_sin[(size_t)pos * half + d];
             const float lo = v * c - b * s, hi = b * c + v * s;
             if (epi == EPI_ROPE_Q) {
@@ -471,7 +476,20 @@ hipError_t launch_gemm(const PfGemm& g, hipStream_t s) {
   }
   // 64-row tiles while 128-row tiles would leave fewer than about two per compute unit
   const long tiles128 = (long)((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM);
-  const bool rows64 = g.tile_rows == 64 || (g.tile_rows != 128 && tiles128 < 600);
+  const bool rows64 = g.tile_rows == 64 || g.tile_rows == 160 || (g.tile_rows != 128 && tiles128 < 600);
+  if constexpr (EPI == EPI_RESID) {
+    // Tiles of 160 columns where they divide the width and fill the resident workgroups (two per compute
+    // unit, 512 on this chip) in fewer, fuller rounds: 1024 rows x 5120 columns are 640 tiles of 64 x 128,
+    // i.e. one full round and a quarter of one, but 512 tiles of 64 x 160, exactly one round.
+    if (rows64 && g.N % 160 == 0) {
+      const long t128 = (long)(g.N / BN) * ((g.M + 63) / 64), t160 = (long)(g.N / 160) * ((g.M + 63) / 64);
+      const long cost128 = ((t128 + 511) / 512) * 128, cost160 = ((t160 + 511) / 512) * 160;
+      if (g.tile_rows == 160 || (g.tile_rows == 0 && cost160 < cost128)) {
+        pf_gemm_kernel<T, EPI, 64, 160><<<dim3((unsigned)t160), dim3(256), 0, s>>>(g);
+        return hipGetLastError();
+      }
+    }
+  }
   if (rows64) {
     dim3 grid(((g.N + BN - 1) / BN) * ((g.M + 63) / 64));
     pf_gemm_kernel<T, EPI, 64><<<grid, dim3(256), 0, s>>>(g);

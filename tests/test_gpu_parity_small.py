@@ -255,13 +255,20 @@ def test_prefill_hidden_states_and_cache(name, n_prompt):
     gm.close()
 
 
-@pytest.mark.parametrize("name", ["c1", "c1-bf16", "gqa-hd128-bf16"])
+WIDE160 = W.Workload(_tiny("bf16", name="wide160", n_q_heads=5, n_kv_heads=5, head_dim=128, d_model=640, ffn_dim=1296,
+                           vocab=1040, n_layers=3),
+                     exit_layer=1, draft_len=4, n_prompt=300, n_new=20, resid_scale=0.1, gain_jitter=0.1)
+
+
+@pytest.mark.parametrize("name", ["c1", "c1-bf16", "gqa-hd128-bf16", "gqa2-f32", "wide160-bf16"])
 def test_every_prompt_pass_shape_matches_oracle(name):
-    """ls_set_prompt_tiles: the prompt GEMMs with 128-, 64- and 32-row output tiles and the 16-row
-    passes of the decode kernel, each forced on a prompt that spans several tiles of every height
-    with a ragged last one (300 = 2 x 128 + 44 = 4 x 64 + 44 = 9 x 32 + 12 = 18 x 16 + 12)."""
+    """ls_set_prompt_tiles: the prompt GEMMs with 128-, 64- and 32-row output tiles, with 64 x 160 tiles
+    in the products into the residual rows (d_model 320 and 640 are multiples of 160; elsewhere the
+    setting falls back to 64 x 128), and the 16-row passes of the decode kernel, each forced on a prompt
+    that spans several tiles of every height with a ragged last one
+    (300 = 2 x 128 + 44 = 4 x 64 + 44 = 9 x 32 + 12 = 18 x 16 + 12)."""
     n_prompt = 300
-    w = CASES[name].with_(n_prompt=n_prompt)
+    w = (WIDE160 if name == "wide160-bf16" else CASES[name]).with_(n_prompt=n_prompt)
     ws, prompt, om, gm = _setup(w, max_seq=n_prompt + 64)
     hid = []
     cache = om.new_cache(n_prompt + 64)
@@ -273,7 +280,7 @@ def test_every_prompt_pass_shape_matches_oracle(name):
     from paper_2404_16710_amd.binding import LsError
     with pytest.raises(LsError):
         gm.set_prompt_tiles(48)
-    for rows in (128, 64, 32, 16, 0):
+    for rows in (128, 64, 160, 32, 16, 0):
         print(f"[prompt tiles] {name} rows {rows}", flush=True)
         gm.set_prompt_tiles(rows)
         cap.zero_()
