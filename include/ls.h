@@ -212,8 +212,10 @@ int ls_debug_spin_limit(ls_ctx *ctx, int32_t polls);
  * instantiations of the attention stage, and tests use it to run both on one model.  LS_E_RANGE otherwise. */
 int ls_debug_kv_policy(ls_ctx *ctx, int32_t policy);
 
-/* Launch shape: workgroups per compute unit (1 or 2) used by later calls; 0 restores the default.
- * Returns the number of workgroups a launch will use, or a negative error. */
+/* Launch shape: workgroups per compute unit used by later calls, from 1 to what the kernels' LDS and
+ * register footprint lets a compute unit hold (the occupancy the runtime reports at load time; 1 with
+ * the present 142 KB of LDS per workgroup); 0 restores the default, the maximum.  Returns the number
+ * of workgroups a launch will use, or LS_E_RANGE for a count the device cannot keep resident. */
 int ls_set_launch(ls_ctx *ctx, int32_t workgroups_per_cu);
 
 /* Shape of the prompt pass used by later calls.  Prompts of 32 or more ids run as GEMMs over all
